@@ -1,0 +1,97 @@
+/*
+ * C ABI of the MI355X (gfx950) fused attention library: exact scaled-dot-product
+ * attention, forward and backward, bf16 storage, fp32 accumulation.
+ *
+ * What is computed (paper Sec. 2.1):
+ *   forward   S = scale * Q K^T (+ causal mask), P = softmax_rows(S), O = P V,
+ *             LSE_i = ln sum_j exp(S_ij)   (natural log, of the scaled, masked scores)
+ *   backward  dV = P^T dO, dP = dO V^T, dS = P o (dP - D), D_i = sum_c dO_ic O_ic,
+ *             dQ = scale * dS K, dK = scale * dS^T Q
+ * The N x N matrices S, P, dP, dS never reach device memory; the forward pass keeps
+ * tiled online-softmax statistics with thresholded rescaling (paper Sec. 3.1.4) and the
+ * backward pass recomputes P from Q, K and LSE (paper Sec. 3.2).
+ *
+ * Conventions shared by every entry point
+ *   - Every pointer is a DEVICE pointer owned by the caller.  The library never
+ *     allocates, frees or keeps it.  `stream` is a hipStream_t passed as void*
+ *     (NULL = the default stream).  Calls only enqueue work on `stream` and return.
+ *   - Layouts are contiguous row-major ("token-major"):
+ *       q, o, d_o, dq : [B, N, H,   d]   bf16      (d = d_qk for q/dq, d_v for o/d_o)
+ *       k, dk         : [B, N, Hkv, d_qk] bf16
+ *       v, dv         : [B, N, Hkv, d_v]  bf16
+ *       lse           : [B, H, N]         fp32
+ *     bf16 = upper 16 bits of an IEEE fp32; outputs are rounded to nearest even.
+ *     All pointers must be 16-byte aligned.
+ *   - Grouped-query attention: H % Hkv == 0; query head h reads KV head h / (H / Hkv);
+ *     dk and dv are summed over the query heads of each group.
+ *   - causal != 0: key j is visible to query i iff j <= i.
+ *   - Supported shapes: (d_qk, d_v) in {(64,64), (128,128), (192,128)}; N a positive
+ *     multiple of 128.
+ *   - Return value: ATTN_OK, or a negative code.  On any error nothing has been
+ *     enqueued and no output has been touched.
+ *   - Re-entrant; no global state.  Calls on different streams may run concurrently
+ *     as long as their outputs and workspaces do not overlap.
+ */
+#ifndef PAPER_2603_05451_AMD_ATTN_H
+#define PAPER_2603_05451_AMD_ATTN_H
+
+#include <stddef.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+    ATTN_OK = 0,
+    ATTN_EINVAL = -1,       /* null pointer, non-positive size, H % Hkv != 0, misaligned pointer,
+                               workspace too small */
+    ATTN_EUNSUPPORTED = -2, /* head dims or N outside the supported set */
+    ATTN_ELAUNCH = -3       /* the HIP runtime refused a launch */
+};
+
+/* Forward pass (paper Sec. 2.1 first display; tiled evaluation per Sec. 3.1.4).
+ *   in : q [B,N,H,d_qk], k [B,N,Hkv,d_qk], v [B,N,Hkv,d_v]   bf16, device
+ *   out: o [B,N,H,d_v] bf16, lse [B,H,N] fp32                 device
+ * attn_fwd is attn_fwd_ex with d_qk = d_v = d. */
+int attn_fwd(const void* q, const void* k, const void* v, void* o, float* lse,
+             int B, int H, int Hkv, int N, int d, float scale, int causal, void* stream);
+int attn_fwd_ex(const void* q, const void* k, const void* v, void* o, float* lse,
+                int B, int H, int Hkv, int N, int d_qk, int d_v, float scale, int causal,
+                void* stream);
+
+/* Backward pass (paper Sec. 2.1 second display; loop structure per Sec. 3.2.2:
+ * one workgroup per KV tile, dK/dV accumulated on chip, dQ accumulated across KV
+ * tiles in fp32 in the workspace and converted at the end).
+ *   in : q, k, v as above; o, d_o [B,N,H,d_v] bf16; lse [B,H,N] fp32 -- o and lse
+ *        must be the outputs of the forward call with the same arguments
+ *   out: dq [B,N,H,d_qk], dk [B,N,Hkv,d_qk], dv [B,N,Hkv,d_v]  bf16
+ *   workspace: device scratch of at least attn_bwd_workspace_bytes(...) bytes,
+ *        256-byte aligned; contents on entry are ignored, contents on exit are
+ *        unspecified; may be reused by the next call on the same stream.
+ * Three kernels are enqueued: D = rowsum(dO o O) (which also clears the fp32 dQ
+ * accumulator), the main kernel, and the dQ conversion.  dQ is summed with fp32
+ * atomics, so its low-order bits can differ from run to run (paper Sec. 3.2.4
+ * names the same property). */
+int attn_bwd(const void* q, const void* k, const void* v, const void* o, const void* d_o,
+             const float* lse, void* dq, void* dk, void* dv,
+             int B, int H, int Hkv, int N, int d, float scale, int causal,
+             void* workspace, size_t workspace_bytes, void* stream);
+int attn_bwd_ex(const void* q, const void* k, const void* v, const void* o, const void* d_o,
+                const float* lse, void* dq, void* dk, void* dv,
+                int B, int H, int Hkv, int N, int d_qk, int d_v, float scale, int causal,
+                void* workspace, size_t workspace_bytes, void* stream);
+
+/* Bytes of workspace attn_bwd(_ex) needs for these sizes (0 if they are invalid):
+ * the fp32 dQ accumulator [B,N,H,d_qk] plus D and the base-2 LSE, [B,H,N] fp32 each. */
+size_t attn_bwd_workspace_bytes(int B, int H, int Hkv, int N, int d_qk, int d_v);
+
+/* Human-readable text for a return code (static storage). */
+const char* attn_strerror(int code);
+
+/* Library version: major * 10000 + minor * 100 + patch. */
+int attn_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif

@@ -1,0 +1,127 @@
+"""MI355X-native fused attention (forward + backward): thin Python binding of libattn.so.
+
+Argument marshalling only: every step of the path runs in the HIP kernels behind the C ABI
+declared in include/attn.h.  PyTorch supplies device memory and streams.  There is no CPU
+or eager fallback: if the library is missing or a call fails, an exception is raised.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libattn.so")
+_lib = None
+
+ATTN_OK, ATTN_EINVAL, ATTN_EUNSUPPORTED, ATTN_ELAUNCH = 0, -1, -2, -3
+
+
+class AttnError(RuntimeError):
+    def __init__(self, code: int, text: str):
+        super().__init__(f"libattn error {code}: {text}")
+        self.code = code
+
+
+def lib():
+    """Load libattn.so (built in-tree by build.py); fail loudly when it is absent."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise ImportError(f"{LIB_PATH} not found: run `python -m paper_2603_05451_amd.build` "
+                              "(hipcc --offload-arch=gfx950); there is no fallback path")
+        L = ctypes.CDLL(LIB_PATH)
+        vp, i, f, sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_float, ctypes.c_size_t
+        L.attn_fwd.argtypes = [vp, vp, vp, vp, vp, i, i, i, i, i, f, i, vp]
+        L.attn_fwd.restype = i
+        L.attn_fwd_ex.argtypes = [vp, vp, vp, vp, vp, i, i, i, i, i, i, f, i, vp]
+        L.attn_fwd_ex.restype = i
+        L.attn_bwd.argtypes = [vp] * 9 + [i, i, i, i, i, f, i, vp, sz, vp]
+        L.attn_bwd.restype = i
+        L.attn_bwd_ex.argtypes = [vp] * 9 + [i, i, i, i, i, i, f, i, vp, sz, vp]
+        L.attn_bwd_ex.restype = i
+        L.attn_bwd_workspace_bytes.argtypes = [i] * 6
+        L.attn_bwd_workspace_bytes.restype = sz
+        L.attn_strerror.argtypes = [i]
+        L.attn_strerror.restype = ctypes.c_char_p
+        L.attn_version.restype = i
+        _lib = L
+    return _lib
+
+
+def attn_strerror(code: int) -> str:
+    return lib().attn_strerror(int(code)).decode()
+
+
+def attn_version() -> int:
+    return int(lib().attn_version())
+
+
+def _check(rc: int):
+    if rc != ATTN_OK:
+        raise AttnError(rc, attn_strerror(rc))
+
+
+def _stream(stream):
+    import torch
+    s = torch.cuda.current_stream() if stream is None else stream
+    return ctypes.c_void_p(s.cuda_stream)
+
+
+def _dev_bf16(t, name, shape=None):
+    import torch
+    if not (t.is_cuda and t.dtype == torch.bfloat16 and t.is_contiguous()):
+        raise ValueError(f"{name} must be a contiguous bf16 CUDA tensor")
+    if shape is not None and tuple(t.shape) != tuple(shape):
+        raise ValueError(f"{name} has shape {tuple(t.shape)}, expected {tuple(shape)}")
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def attn_bwd_workspace_bytes(B, H, Hkv, N, d_qk, d_v) -> int:
+    return int(lib().attn_bwd_workspace_bytes(B, H, Hkv, N, d_qk, d_v))
+
+
+def attn_fwd(q, k, v, scale, causal, o=None, lse=None, stream=None):
+    """q [B,N,H,d_qk], k [B,N,Hkv,d_qk], v [B,N,Hkv,d_v] bf16 on the GPU -> (o [B,N,H,d_v] bf16,
+    lse [B,H,N] fp32).  Outputs are allocated with torch unless passed in."""
+    import torch
+    B, N, H, dqk = q.shape
+    Hkv, dv = k.shape[2], v.shape[3]
+    if o is None:
+        o = torch.empty((B, N, H, dv), dtype=torch.bfloat16, device=q.device)
+    if lse is None:
+        lse = torch.empty((B, H, N), dtype=torch.float32, device=q.device)
+    if not (lse.is_cuda and lse.dtype == torch.float32 and lse.is_contiguous() and
+            tuple(lse.shape) == (B, H, N)):
+        raise ValueError("lse must be a contiguous fp32 CUDA tensor [B,H,N]")
+    rc = lib().attn_fwd_ex(_dev_bf16(q, "q"), _dev_bf16(k, "k", (B, N, Hkv, dqk)),
+                           _dev_bf16(v, "v", (B, N, Hkv, dv)), _dev_bf16(o, "o", (B, N, H, dv)),
+                           ctypes.c_void_p(lse.data_ptr()), B, H, Hkv, N, dqk, dv,
+                           float(scale), int(bool(causal)), _stream(stream))
+    _check(rc)
+    return o, lse
+
+
+def attn_bwd(q, k, v, o, do, lse, scale, causal, dq=None, dk=None, dv=None, workspace=None,
+             stream=None):
+    """Gradients dq, dk, dv (bf16, layouts of q, k, v) from do, the forward's o and lse."""
+    import torch
+    B, N, H, dqk = q.shape
+    Hkv, dvd = k.shape[2], v.shape[3]
+    dq = torch.empty_like(q) if dq is None else dq
+    dk = torch.empty_like(k) if dk is None else dk
+    dv = torch.empty_like(v) if dv is None else dv
+    need = attn_bwd_workspace_bytes(B, H, Hkv, N, dqk, dvd)
+    if need == 0:
+        _check(lib().attn_bwd_ex(*([None] * 9), B, H, Hkv, N, dqk, dvd, float(scale), 0, None, 0, None)
+               or ATTN_EINVAL)
+    if workspace is None:
+        workspace = torch.empty(need, dtype=torch.uint8, device=q.device)
+    rc = lib().attn_bwd_ex(_dev_bf16(q, "q"), _dev_bf16(k, "k", (B, N, Hkv, dqk)),
+                           _dev_bf16(v, "v", (B, N, Hkv, dvd)), _dev_bf16(o, "o", (B, N, H, dvd)),
+                           _dev_bf16(do, "do", (B, N, H, dvd)), ctypes.c_void_p(lse.data_ptr()),
+                           _dev_bf16(dq, "dq", q.shape), _dev_bf16(dk, "dk", k.shape),
+                           _dev_bf16(dv, "dv", v.shape), B, H, Hkv, N, dqk, dvd, float(scale),
+                           int(bool(causal)), ctypes.c_void_p(workspace.data_ptr()),
+                           workspace.numel() * workspace.element_size(), _stream(stream))
+    _check(rc)
+    return dq, dk, dv

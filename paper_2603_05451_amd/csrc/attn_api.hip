@@ -1,0 +1,123 @@
+// C ABI of the attention library: argument validation, workspace carving, dispatch.
+// See include/attn.h for the contract of every entry point.
+#include "../../include/attn.h"
+#include "launch.h"
+
+#include <stdint.h>
+
+namespace {
+
+bool dims_supported(int d_qk, int d_v)
+{
+    return (d_qk == 64 && d_v == 64) || (d_qk == 128 && d_v == 128) || (d_qk == 192 && d_v == 128);
+}
+
+bool misaligned(const void* p, uintptr_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) != 0; }
+
+int check_sizes(int B, int H, int Hkv, int N, int d_qk, int d_v)
+{
+    if (B <= 0 || H <= 0 || Hkv <= 0 || N <= 0 || d_qk <= 0 || d_v <= 0) return ATTN_EINVAL;
+    if (H % Hkv != 0) return ATTN_EINVAL;
+    if (!dims_supported(d_qk, d_v)) return ATTN_EUNSUPPORTED;
+    if (N % 128 != 0) return ATTN_EUNSUPPORTED;
+    // element offsets are 64-bit, but row indices B*N*H must fit a 32-bit grid
+    if ((int64_t)B * H * (N / 128) > 0x7fffffffLL) return ATTN_EUNSUPPORTED;
+    return ATTN_OK;
+}
+
+size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+struct WorkspaceLayout {
+    size_t dq_acc_off, d_off, lse2_off, total;
+};
+
+WorkspaceLayout workspace_layout(int B, int H, int N, int d_qk)
+{
+    WorkspaceLayout w;
+    const size_t rows = (size_t)B * H * N;
+    w.dq_acc_off = 0;
+    w.d_off = align_up(rows * (size_t)d_qk * sizeof(float), 256);
+    w.lse2_off = w.d_off + align_up(rows * sizeof(float), 256);
+    w.total = w.lse2_off + align_up(rows * sizeof(float), 256);
+    return w;
+}
+
+}  // namespace
+
+extern "C" {
+
+int attn_fwd_ex(const void* q, const void* k, const void* v, void* o, float* lse,
+                int B, int H, int Hkv, int N, int d_qk, int d_v, float scale, int causal,
+                void* stream)
+{
+    if (!q || !k || !v || !o || !lse) return ATTN_EINVAL;
+    if (int rc = check_sizes(B, H, Hkv, N, d_qk, d_v)) return rc;
+    if (!(scale > 0.0f) || !(scale < 1e30f)) return ATTN_EINVAL;
+    if (misaligned(q, 16) || misaligned(k, 16) || misaligned(v, 16) || misaligned(o, 16) ||
+        misaligned(lse, 4))
+        return ATTN_EINVAL;
+    attn::FwdArgs a{q, k, v, o, lse, B, H, Hkv, N, d_qk, d_v, scale, causal != 0, stream};
+    const int rc = attn::launch_fwd(a);
+    return rc == 0 ? ATTN_OK : (rc == -2 ? ATTN_EUNSUPPORTED : ATTN_ELAUNCH);
+}
+
+int attn_fwd(const void* q, const void* k, const void* v, void* o, float* lse,
+             int B, int H, int Hkv, int N, int d, float scale, int causal, void* stream)
+{
+    return attn_fwd_ex(q, k, v, o, lse, B, H, Hkv, N, d, d, scale, causal, stream);
+}
+
+size_t attn_bwd_workspace_bytes(int B, int H, int Hkv, int N, int d_qk, int d_v)
+{
+    if (check_sizes(B, H, Hkv, N, d_qk, d_v) != ATTN_OK) return 0;
+    return workspace_layout(B, H, N, d_qk).total;
+}
+
+int attn_bwd_ex(const void* q, const void* k, const void* v, const void* o, const void* d_o,
+                const float* lse, void* dq, void* dk, void* dv,
+                int B, int H, int Hkv, int N, int d_qk, int d_v, float scale, int causal,
+                void* workspace, size_t workspace_bytes, void* stream)
+{
+    if (!q || !k || !v || !o || !d_o || !lse || !dq || !dk || !dv || !workspace) return ATTN_EINVAL;
+    if (int rc = check_sizes(B, H, Hkv, N, d_qk, d_v)) return rc;
+    if (!(scale > 0.0f) || !(scale < 1e30f)) return ATTN_EINVAL;
+    const void* ptrs[] = {q, k, v, o, d_o, dq, dk, dv};
+    for (const void* p : ptrs)
+        if (misaligned(p, 16)) return ATTN_EINVAL;
+    if (misaligned(lse, 4) || misaligned(workspace, 256)) return ATTN_EINVAL;
+    const WorkspaceLayout w = workspace_layout(B, H, N, d_qk);
+    if (workspace_bytes < w.total) return ATTN_EINVAL;
+    char* ws = static_cast<char*>(workspace);
+    attn::BwdArgs a{q, k, v, o, d_o, lse, dq, dk, dv, B, H, Hkv, N, d_qk, d_v, scale, causal != 0,
+                    reinterpret_cast<float*>(ws + w.dq_acc_off),
+                    reinterpret_cast<float*>(ws + w.d_off),
+                    reinterpret_cast<float*>(ws + w.lse2_off), stream};
+    const int rc = attn::launch_bwd(a);
+    return rc == 0 ? ATTN_OK : (rc == -2 ? ATTN_EUNSUPPORTED : ATTN_ELAUNCH);
+}
+
+int attn_bwd(const void* q, const void* k, const void* v, const void* o, const void* d_o,
+             const float* lse, void* dq, void* dk, void* dv,
+             int B, int H, int Hkv, int N, int d, float scale, int causal,
+             void* workspace, size_t workspace_bytes, void* stream)
+{
+    return attn_bwd_ex(q, k, v, o, d_o, lse, dq, dk, dv, B, H, Hkv, N, d, d, scale, causal,
+                       workspace, workspace_bytes, stream);
+}
+
+const char* attn_strerror(int code)
+{
+    switch (code) {
+        case ATTN_OK: return "success";
+        case ATTN_EINVAL: return "invalid argument (null or misaligned pointer, bad size, H % Hkv != 0, "
+                                 "non-positive scale, or workspace too small)";
+        case ATTN_EUNSUPPORTED: return "unsupported shape: (d_qk, d_v) must be (64,64), (128,128) or "
+                                       "(192,128) and N a multiple of 128";
+        case ATTN_ELAUNCH: return "HIP kernel launch failed";
+        default: return "unknown error code";
+    }
+}
+
+int attn_version(void) { return 100; }
+
+}  // extern "C"

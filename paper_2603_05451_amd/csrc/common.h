@@ -1,0 +1,136 @@
+// Shared device-side vocabulary for the gfx950 attention kernels: vector types, the
+// MFMA wrappers with their register layouts spelled out, LDS tile addressing and the
+// asynchronous global->LDS tile copy.  HIP/CDNA4 only.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace attn {
+
+typedef __bf16 bf16;
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+typedef __attribute__((ext_vector_type(4))) short s16x4;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+
+#define ATTN_LDS __attribute__((address_space(3)))
+
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kLn2 = 0.6931471805599453f;
+// Threshold of the conditional rescale in base-2 units (paper Sec. 3.1.4: log2(256)).
+constexpr float kRescaleTau = 8.0f;
+
+// v_mfma_f32_32x32x16_bf16, D = A(32x16) * B(16x32) + C.  Lane l = 32*h + c:
+//   A: row c,  k = 8h..8h+7           B: column c, k = 8h..8h+7
+//   C/D register r: row 8*(r/4) + 4h + r%4, column c.
+// A permutation of k applied to A and B alike leaves the product unchanged.
+__device__ __forceinline__ f32x16 mfma32(bf16x8 a, bf16x8 b, f32x16 c)
+{
+    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+}
+
+// Row of a 32x32 accumulator register r for lane half h.
+__device__ __forceinline__ constexpr int acc_row(int r, int h) { return 8 * (r >> 2) + 4 * h + (r & 3); }
+
+// max / sum with the lane 32 apart (v_permlane32_swap exchanges the upper half of the first
+// operand with the lower half of the second).
+__device__ __forceinline__ float xhalf_max(float x)
+{
+    auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+__device__ __forceinline__ float xhalf_sum(float x)
+{
+    auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+__device__ __forceinline__ float fast_log2(float x) { return __builtin_amdgcn_logf(x); }
+
+// ---------------------------------------------------------------------------------------
+// LDS tiles.  A tile holds ROWS rows of D bf16 (D/8 chunks of 16 bytes per row), rows
+// contiguous, chunks XOR-swizzled inside a row so that both access patterns below are
+// bank-conflict free with no padding (padding is impossible: the global->LDS copy writes
+// 64 consecutive 16-byte chunks per wave instruction).
+//
+//   row pattern : one 16-byte chunk per lane, 16 consecutive lanes = 16 consecutive rows,
+//                 same logical chunk (MFMA operand contracted over the head dimension);
+//   tr pattern  : ds_read_b64_tr_b16, 16 lanes fetch 4 consecutive rows x 32 bytes, a pair
+//                 of such groups covers 4 rows x 64 bytes = one aligned group of 4 chunks
+//                 (MFMA operand contracted over the row index).
+//
+// Banks repeat every 256 bytes = 16 chunks.  With 16 chunks per row (D = 128) every row
+// starts at bank 0, so the XOR value must (a) take 16 distinct values over 16 consecutive
+// rows and (b) move the aligned 4-chunk group to 4 distinct groups over 4 consecutive
+// rows: x = ((row & 3) << 2) | ((row >> 2) & 3).  With 8 or 24 chunks per row (D = 64,
+// 192) rows alternate between bank 0 and bank 32, the XOR stays inside an aligned group
+// of 8 chunks, and the same two conditions give, with y = row >> 1,
+// x = ((y & 1) << 2) | ((y >> 1) & 3).
+// ---------------------------------------------------------------------------------------
+template <int D>
+__device__ __forceinline__ int swz_chunk(int row, int chunk)
+{
+    constexpr int CPR = D / 8;
+    if constexpr (CPR % 16 == 0) {
+        return chunk ^ (((row & 3) << 2) | ((row >> 2) & 3));
+    } else {
+        const int y = row >> 1;
+        return chunk ^ (((y & 1) << 2) | ((y >> 1) & 3));
+    }
+}
+
+// Byte offset of logical 16-byte chunk `chunk` of row `row`.
+template <int D>
+__device__ __forceinline__ int tile_off(int row, int chunk)
+{
+    return (row * (D / 8) + swz_chunk<D>(row, chunk)) * 16;
+}
+
+// Asynchronous copy of a ROWS x D bf16 tile from global memory (row stride `gstride`
+// elements) into an LDS tile, by all NT threads of the block.  No VGPR staging: each
+// wave instruction moves 64 x 16 bytes straight into LDS.  Completion is observed with
+// s_waitcnt vmcnt(0) followed by a workgroup barrier.
+template <int ROWS, int D, int NT>
+__device__ __forceinline__ void tile_load_async(const bf16* __restrict__ g, int64_t gstride,
+                                                ATTN_LDS char* lds, int tid)
+{
+    constexpr int CPR = D / 8;
+    constexpr int NCHUNK = ROWS * CPR;
+    static_assert(NCHUNK % NT == 0, "tile must be a whole number of block-wide copies");
+    const int wave = tid >> 6, lane = tid & 63;
+#pragma unroll
+    for (int t = 0; t < NCHUNK / NT; ++t) {
+        const int p0 = (t * (NT / 64) + wave) * 64;   // first chunk this wave instruction writes
+        const int p = p0 + lane;
+        const int row = p / CPR;
+        const int chunk = swz_chunk<D>(row, p % CPR);   // XOR is its own inverse
+        const bf16* src = g + (int64_t)row * gstride + chunk * 8;
+        __builtin_amdgcn_global_load_lds((const void*)src, (ATTN_LDS void*)(lds + p0 * 16), 16, 0, 0);
+    }
+}
+
+__device__ __forceinline__ void wait_async_copies() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+
+__device__ __forceinline__ bf16x8 lds_read_b128(const ATTN_LDS char* p)
+{
+    return *(const ATTN_LDS bf16x8*)p;
+}
+
+// ds_read_b64_tr_b16: within each group of 16 lanes, lane i receives element (i % 4) of the
+// 8-byte rows fetched by lanes i/4, 4 + i/4, 8 + i/4, 12 + i/4 of the group.
+__device__ __forceinline__ bf16x4 lds_read_tr(const ATTN_LDS char* p)
+{
+    s16x4 r = __builtin_amdgcn_ds_read_tr16_b64_v4i16((ATTN_LDS s16x4*)p);
+    return __builtin_bit_cast(bf16x4, r);
+}
+
+__device__ __forceinline__ bf16x8 cat4(bf16x4 a, bf16x4 b)
+{
+    return __builtin_shufflevector(a, b, 0, 1, 2, 3, 4, 5, 6, 7);
+}
+
+}  // namespace attn

@@ -1,0 +1,64 @@
+"""GPU parity of the forward pass against the CPU fp64 oracle, through the C ABI."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2603_05451_amd import inputs as I
+from parity import LSE_ABS, assert_close, assert_close_outlier
+
+pytestmark = pytest.mark.gpu
+
+
+def gpu_fwd(w, x):
+    import paper_2603_05451_amd as A
+    q, k, v = (x[n].cuda() for n in ("q", "k", "v"))
+    o, lse = A.attn_fwd(q, k, v, w.scale, w.causal)
+    torch.cuda.synchronize()
+    return o.float().cpu().numpy(), lse.cpu().numpy()
+
+
+SMALL = [
+    I.CANARY,
+    I.Workload("s_d64_c", 2, 4, 2, 384, 64, 64, True, 11),
+    I.Workload("s_d64_nc", 1, 3, 1, 256, 64, 64, False, 12),
+    I.Workload("s_d128_nc", 2, 4, 4, 384, 128, 128, False, 13),
+    I.Workload("s_d128_c", 2, 4, 2, 640, 128, 128, True, 14),
+    I.Workload("s_d192_c", 1, 4, 2, 384, 192, 128, True, 15),
+    I.Workload("s_d192_nc", 1, 2, 2, 256, 192, 128, False, 16),
+    I.Workload("s_d192_c_outl", 1, 2, 1, 512, 192, 128, True, 17, outlier_frac=0.01),
+]
+
+
+@pytest.mark.parametrize("w", SMALL, ids=lambda w: w.name)
+def test_fwd_small_full_parity(oracle, w):
+    x = I.make_inputs(w, with_do=False)
+    o, lse = gpu_fwd(w, x)
+    ro, rlse = oracle.attn_fwd(I.to_f64(x["q"]), I.to_f64(x["k"]), I.to_f64(x["v"]), w.scale, w.causal)
+    (assert_close_outlier if w.outlier_frac else assert_close)(o, ro, f"O {w.name}")
+    assert np.abs(lse - rlse).max() <= LSE_ABS, f"LSE {w.name}: {np.abs(lse - rlse).max():.3e}"
+
+
+FULL = [I.TARGET, I.SWEEP_D64_NC[0], I.SWEEP_D64_NC[5], I.SWEEP_D128_C[0], I.SWEEP_D128_C[4], I.GQA,
+        I.MLA_OUTLIER]
+
+
+@pytest.mark.parametrize("w", FULL, ids=lambda w: w.name)
+def test_fwd_full_size_sampled_rows(oracle, w):
+    """At the benchmark sizes the oracle computes sampled query rows one by one (all keys)."""
+    x = I.make_inputs(w, with_do=False)
+    o, lse = gpu_fwd(w, x)
+    assert np.isfinite(o).all() and np.isfinite(lse).all()
+    rng = np.random.default_rng(w.seed)
+    rows = np.unique(np.concatenate([[0, 1, 31, 32, 63, 64, 127, 128, w.N - 129, w.N - 128, w.N - 1],
+                                     rng.integers(0, w.N, 48)]))
+    G = w.H // w.Hkv
+    for b, kvh in {(0, 0), (w.B - 1, w.Hkv - 1)}:
+        hs = slice(kvh * G, (kvh + 1) * G)
+        q = I.to_f64(x["q"][b:b + 1, :, hs][:, rows])
+        k = I.to_f64(x["k"][b:b + 1, :, kvh:kvh + 1])
+        v = I.to_f64(x["v"][b:b + 1, :, kvh:kvh + 1])
+        ro, rlse = oracle.attn_fwd(q, k, v, w.scale, w.causal, q_pos=rows)
+        cmp = assert_close_outlier if w.outlier_frac else assert_close
+        cmp(o[b:b + 1, :, hs][:, rows], ro, f"O {w.name} b{b} kvh{kvh}")
+        err = np.abs(lse[b:b + 1, hs][:, :, rows] - rlse).max()
+        assert err <= LSE_ABS, f"LSE {w.name}: {err:.3e}"
