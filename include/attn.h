@@ -81,6 +81,19 @@ int attn_bwd_ex(const void* q, const void* k, const void* v, const void* o, cons
                 int B, int H, int Hkv, int N, int d_qk, int d_v, float scale, int causal,
                 void* workspace, size_t workspace_bytes, void* stream);
 
+/* attn_bwd_ex restricted to a subset of its three kernels, for per-kernel timing and
+ * profiling (the backward of paper Sec. 3.2 is one logical step; this splits it at the
+ * kernel boundaries).  phases is a bit mask: ATTN_BWD_PREPARE (D, base-2 LSE, clear the dQ
+ * accumulator), ATTN_BWD_MAIN (dK, dV, dQ accumulation), ATTN_BWD_FINISH (dq from the
+ * accumulator).  All arguments as attn_bwd_ex.  Running the three phases in order on one
+ * stream with the same workspace is exactly attn_bwd_ex; running ATTN_BWD_MAIN repeatedly
+ * without ATTN_BWD_PREPARE keeps adding to the accumulator (timing use only). */
+enum { ATTN_BWD_PREPARE = 1, ATTN_BWD_MAIN = 2, ATTN_BWD_FINISH = 4, ATTN_BWD_ALL = 7 };
+int attn_bwd_phases(const void* q, const void* k, const void* v, const void* o, const void* d_o,
+                    const float* lse, void* dq, void* dk, void* dv,
+                    int B, int H, int Hkv, int N, int d_qk, int d_v, float scale, int causal,
+                    void* workspace, size_t workspace_bytes, void* stream, int phases);
+
 /* Bytes of workspace attn_bwd(_ex) needs for these sizes (0 if they are invalid):
  * the fp32 dQ accumulator [B,N,H,d_qk] plus D and the base-2 LSE, [B,H,N] fp32 each. */
 size_t attn_bwd_workspace_bytes(int B, int H, int Hkv, int N, int d_qk, int d_v);

@@ -29,6 +29,10 @@ def lib():
         if not os.path.exists(LIB_PATH):
             raise ImportError(f"{LIB_PATH} not found: run `python -m paper_2603_05451_amd.build` "
                               "(hipcc --offload-arch=gfx950); there is no fallback path")
+        # PyTorch ships its own HIP runtime (same SONAME as the system one).  Load torch first
+        # so that libattn.so binds to the runtime that owns torch's streams and allocations;
+        # two HIP runtimes in one process cannot launch on each other's streams.
+        import torch  # noqa: F401
         L = ctypes.CDLL(LIB_PATH)
         vp, i, f, sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_float, ctypes.c_size_t
         L.attn_fwd.argtypes = [vp, vp, vp, vp, vp, i, i, i, i, i, f, i, vp]
@@ -39,6 +43,8 @@ def lib():
         L.attn_bwd.restype = i
         L.attn_bwd_ex.argtypes = [vp] * 9 + [i, i, i, i, i, i, f, i, vp, sz, vp]
         L.attn_bwd_ex.restype = i
+        L.attn_bwd_phases.argtypes = [vp] * 9 + [i, i, i, i, i, i, f, i, vp, sz, vp, i]
+        L.attn_bwd_phases.restype = i
         L.attn_bwd_workspace_bytes.argtypes = [i] * 6
         L.attn_bwd_workspace_bytes.restype = sz
         L.attn_strerror.argtypes = [i]
@@ -101,9 +107,13 @@ def attn_fwd(q, k, v, scale, causal, o=None, lse=None, stream=None):
     return o, lse
 
 
+ATTN_BWD_PREPARE, ATTN_BWD_MAIN, ATTN_BWD_FINISH, ATTN_BWD_ALL = 1, 2, 4, 7
+
+
 def attn_bwd(q, k, v, o, do, lse, scale, causal, dq=None, dk=None, dv=None, workspace=None,
-             stream=None):
-    """Gradients dq, dk, dv (bf16, layouts of q, k, v) from do, the forward's o and lse."""
+             stream=None, phases=ATTN_BWD_ALL):
+    """Gradients dq, dk, dv (bf16, layouts of q, k, v) from do, the forward's o and lse.
+    phases != ATTN_BWD_ALL maps to attn_bwd_phases (per-kernel timing only)."""
     import torch
     B, N, H, dqk = q.shape
     Hkv, dvd = k.shape[2], v.shape[3]
@@ -116,12 +126,13 @@ def attn_bwd(q, k, v, o, do, lse, scale, causal, dq=None, dk=None, dv=None, work
                or ATTN_EINVAL)
     if workspace is None:
         workspace = torch.empty(need, dtype=torch.uint8, device=q.device)
-    rc = lib().attn_bwd_ex(_dev_bf16(q, "q"), _dev_bf16(k, "k", (B, N, Hkv, dqk)),
-                           _dev_bf16(v, "v", (B, N, Hkv, dvd)), _dev_bf16(o, "o", (B, N, H, dvd)),
-                           _dev_bf16(do, "do", (B, N, H, dvd)), ctypes.c_void_p(lse.data_ptr()),
-                           _dev_bf16(dq, "dq", q.shape), _dev_bf16(dk, "dk", k.shape),
-                           _dev_bf16(dv, "dv", v.shape), B, H, Hkv, N, dqk, dvd, float(scale),
-                           int(bool(causal)), ctypes.c_void_p(workspace.data_ptr()),
-                           workspace.numel() * workspace.element_size(), _stream(stream))
+    rc = lib().attn_bwd_phases(_dev_bf16(q, "q"), _dev_bf16(k, "k", (B, N, Hkv, dqk)),
+                               _dev_bf16(v, "v", (B, N, Hkv, dvd)), _dev_bf16(o, "o", (B, N, H, dvd)),
+                               _dev_bf16(do, "do", (B, N, H, dvd)), ctypes.c_void_p(lse.data_ptr()),
+                               _dev_bf16(dq, "dq", q.shape), _dev_bf16(dk, "dk", k.shape),
+                               _dev_bf16(dv, "dv", v.shape), B, H, Hkv, N, dqk, dvd, float(scale),
+                               int(bool(causal)), ctypes.c_void_p(workspace.data_ptr()),
+                               workspace.numel() * workspace.element_size(), _stream(stream),
+                               int(phases))
     _check(rc)
     return dq, dk, dv

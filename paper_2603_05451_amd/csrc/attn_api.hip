@@ -73,11 +73,12 @@ size_t attn_bwd_workspace_bytes(int B, int H, int Hkv, int N, int d_qk, int d_v)
     return workspace_layout(B, H, N, d_qk).total;
 }
 
-int attn_bwd_ex(const void* q, const void* k, const void* v, const void* o, const void* d_o,
-                const float* lse, void* dq, void* dk, void* dv,
-                int B, int H, int Hkv, int N, int d_qk, int d_v, float scale, int causal,
-                void* workspace, size_t workspace_bytes, void* stream)
+int attn_bwd_phases(const void* q, const void* k, const void* v, const void* o, const void* d_o,
+                    const float* lse, void* dq, void* dk, void* dv,
+                    int B, int H, int Hkv, int N, int d_qk, int d_v, float scale, int causal,
+                    void* workspace, size_t workspace_bytes, void* stream, int phases)
 {
+    if (phases <= 0 || phases > ATTN_BWD_ALL) return ATTN_EINVAL;
     if (!q || !k || !v || !o || !d_o || !lse || !dq || !dk || !dv || !workspace) return ATTN_EINVAL;
     if (int rc = check_sizes(B, H, Hkv, N, d_qk, d_v)) return rc;
     if (!(scale > 0.0f) || !(scale < 1e30f)) return ATTN_EINVAL;
@@ -91,9 +92,18 @@ int attn_bwd_ex(const void* q, const void* k, const void* v, const void* o, cons
     attn::BwdArgs a{q, k, v, o, d_o, lse, dq, dk, dv, B, H, Hkv, N, d_qk, d_v, scale, causal != 0,
                     reinterpret_cast<float*>(ws + w.dq_acc_off),
                     reinterpret_cast<float*>(ws + w.d_off),
-                    reinterpret_cast<float*>(ws + w.lse2_off), stream};
+                    reinterpret_cast<float*>(ws + w.lse2_off), stream, phases};
     const int rc = attn::launch_bwd(a);
     return rc == 0 ? ATTN_OK : (rc == -2 ? ATTN_EUNSUPPORTED : ATTN_ELAUNCH);
+}
+
+int attn_bwd_ex(const void* q, const void* k, const void* v, const void* o, const void* d_o,
+                const float* lse, void* dq, void* dk, void* dv,
+                int B, int H, int Hkv, int N, int d_qk, int d_v, float scale, int causal,
+                void* workspace, size_t workspace_bytes, void* stream)
+{
+    return attn_bwd_phases(q, k, v, o, d_o, lse, dq, dk, dv, B, H, Hkv, N, d_qk, d_v, scale, causal,
+                           workspace, workspace_bytes, stream, ATTN_BWD_ALL);
 }
 
 int attn_bwd(const void* q, const void* k, const void* v, const void* o, const void* d_o,

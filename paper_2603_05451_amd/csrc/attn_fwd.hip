@@ -205,10 +205,10 @@ static int launch_fwd_t(const FwdArgs& a)
         attr_done = true;
     }
     const int grid = a.B * a.H * (a.N / FWD_BM);
-    hipLaunchKernelGGL(kern, dim3(grid), dim3(FWD_NT), smem, (hipStream_t)a.stream,
-                       (const bf16*)a.q, (const bf16*)a.k, (const bf16*)a.v, (bf16*)a.o, a.lse,
-                       a.H, a.Hkv, a.N, a.scale * kLog2e);
-    return hipGetLastError() == hipSuccess ? 0 : -3;
+    const hipError_t e = launch_kernel(kern, dim3(grid), dim3(FWD_NT), smem, a.stream,
+                                       (const bf16*)a.q, (const bf16*)a.k, (const bf16*)a.v, (bf16*)a.o, a.lse,
+                                       a.H, a.Hkv, a.N, a.scale * kLog2e);
+    return e == hipSuccess ? 0 : -3;
 }
 
 int launch_fwd(const FwdArgs& a)

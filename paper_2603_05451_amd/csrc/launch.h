@@ -1,6 +1,8 @@
 // Host-side argument bundles handed from the C ABI to the kernel launchers.
 #pragma once
+#include <hip/hip_runtime.h>
 #include <stddef.h>
+#include <tuple>
 
 namespace attn {
 
@@ -26,7 +28,21 @@ struct BwdArgs {
     float* D;
     float* lse2;
     void* stream;
+    int phases;   // bit mask: 1 prepare, 2 main, 4 finish
 };
+
+// Launch through hipLaunchKernel so that the status returned belongs to THIS launch (the
+// sticky hipGetLastError slot may hold an unrelated earlier error of the host program).
+template <typename... KArgs, typename... Args>
+inline hipError_t launch_kernel(void (*kern)(KArgs...), dim3 grid, dim3 block, size_t smem, void* stream,
+                                Args... args)
+{
+    std::tuple<KArgs...> vals{static_cast<KArgs>(args)...};
+    void* ptrs[sizeof...(KArgs)];
+    int n = 0;
+    std::apply([&](auto&... v) { ((ptrs[n++] = (void*)&v), ...); }, vals);
+    return hipLaunchKernel((const void*)kern, grid, block, ptrs, smem, (hipStream_t)stream);
+}
 
 // 0 on success, -2 unsupported head dims, -3 launch failure.
 int launch_fwd(const FwdArgs& a);

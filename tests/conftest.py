@@ -17,3 +17,11 @@ def oracle():
     import oracle as _oracle
     _oracle.build()
     return _oracle
+
+
+def pytest_sessionfinish(session, exitstatus):
+    try:
+        import parity
+        parity.dump_report(os.path.join(ROOT, "gpurun_out", "parity_errors.txt"))
+    except Exception:
+        pass

@@ -1,12 +1,33 @@
-"""Comparison helpers for the GPU parity tests: the tolerance of the benchmark spec
-(bf16 outputs and gradients within max-abs 2e-2 and relative Frobenius 1e-2 of the fp64
-oracle on N(0,1) inputs), written once."""
+"""Comparison helpers for the GPU parity tests.
+
+Tolerance of the benchmark spec, written once: bf16 outputs and gradients within max-abs
+2e-2 and relative Frobenius 1e-2 of the fp64 oracle on N(0,1) inputs.
+
+The heavy-tailed workload (1 % of Q and K entries multiplied by 8) is outside the "N(0,1)
+inputs" premise: a single bf16 half-ulp exceeds 2e-2 once |x| >= 8, and the gradients are
+sums of large cancelling terms (sum_j dS_ij = 0) whose bf16 rounding error (P and dS are
+bf16 MFMA operands, relative error 2^-9 each, as in the paper's kernels) is proportional to
+the size of the TERMS, not of the result.  The backward pass also reads the forward's bf16 O
+to form D_i = dO_i . O_i, so D_i carries an error of up to 2^-9 sum_c |dO_ic O_ic| =: 2^-9 E_i,
+which enters dS_ij as P_ij dD_i and hence dQ_i as scale dD_i sum_j P_ij K_j and dK_j as
+scale sum_i P_ij dD_i Q_i.  For that workload the elementwise gate is the first-order bound of
+these three rounding sites with a factor 2 of slack,
+    |got - ref| <= 2e-2 + 2^-8 (|ref| + A)
+    A_O  = P |V|                      A_dV = P^T |dO|
+    A_dQ = scale (|dS| |K| + E (P |K|))        A_dK = scale (|dS|^T |Q| + P^T (E |Q|))
+and the relative Frobenius bound 1e-2 is kept unchanged.  term_magnitudes() evaluates A with
+numpy; it only scales a tolerance and produces no expected value.
+"""
+import os
+
 import numpy as np
 
 MAX_ABS = 2e-2
 REL_FRO = 1e-2
 # LSE is fp32 and of size O(ln N + |S|): a pure fp32 quantity, held to a much tighter bound.
 LSE_ABS = 2e-3
+
+REPORT = []   # (what, max_abs, rel_fro) of every comparison, dumped by conftest at session end
 
 
 def errors(got, ref):
@@ -20,18 +41,53 @@ def errors(got, ref):
 
 def assert_close(got, ref, what, max_abs=MAX_ABS, rel_fro=REL_FRO):
     ma, rf = errors(got, ref)
+    REPORT.append((what, ma, rf))
     assert ma <= max_abs and rf <= rel_fro, f"{what}: max-abs {ma:.3e} (<= {max_abs}), rel-Fro {rf:.3e} (<= {rel_fro})"
     return ma, rf
 
 
-def assert_close_outlier(got, ref, what):
-    """Heavy-tailed inputs (the x8 outlier workload): gradients can exceed 8 in magnitude, where
-    one bf16 half-ulp alone is 2e-2.  Gate elementwise on 2e-2 + 2^-8 |ref| and on the same
-    relative Frobenius bound."""
+def assert_close_terms(got, ref, mag, what):
+    """Gate for the heavy-tailed workload: see the module docstring.  mag = A, same shape."""
     got = np.asarray(got, dtype=np.float64)
     ref = np.asarray(ref, dtype=np.float64)
-    assert np.isfinite(got).all(), "non-finite values in GPU result"
-    excess = np.abs(got - ref) - (MAX_ABS + 2.0 ** -8 * np.abs(ref))
     ma, rf = errors(got, ref)
-    assert excess.max() <= 0 and rf <= REL_FRO, f"{what}: worst excess {excess.max():.3e}, max-abs {ma:.3e}, rel-Fro {rf:.3e}"
+    REPORT.append((what + " [term-scaled gate]", ma, rf))
+    excess = np.abs(got - ref) - (MAX_ABS + 2.0 ** -8 * np.abs(ref) + 2.0 ** -8 * mag)
+    assert excess.max() <= 0 and rf <= REL_FRO, \
+        f"{what}: worst excess {excess.max():.3e}, max-abs {ma:.3e}, rel-Fro {rf:.3e}"
     return ma, rf
+
+
+def term_magnitudes(q, k, v, do, scale, causal, q_pos=None):
+    """Sums of absolute values of the terms of each output element, for ONE batch and ONE KV
+    head: q [Nq,G,dqk], k [Nk,dqk], v [Nk,dv], do [Nq,G,dv] (fp64).  Returns A_O [Nq,G,dv],
+    A_dQ [Nq,G,dqk], A_dK [Nk,dqk], A_dV [Nk,dv].  Used only to scale a tolerance."""
+    Nq, G, _ = q.shape
+    Nk = k.shape[0]
+    pos = np.arange(Nq) if q_pos is None else np.asarray(q_pos)
+    a_o = np.zeros((Nq, G, v.shape[1])); a_dq = np.zeros_like(q)
+    a_dk = np.zeros_like(k); a_dv = np.zeros_like(v)
+    for g in range(G):
+        s = scale * (q[:, g] @ k.T)
+        if causal:
+            s = np.where(np.arange(Nk)[None, :] > pos[:, None], -np.inf, s)
+        p = np.exp(s - s.max(1, keepdims=True))
+        p /= p.sum(1, keepdims=True)
+        dp = do[:, g] @ v.T
+        ds = np.abs(p * (dp - (p * dp).sum(1, keepdims=True)))
+        e = (np.abs(do[:, g]) * np.abs(p @ v)).sum(1, keepdims=True)      # E_i
+        a_o[:, g] = p @ np.abs(v)
+        a_dq[:, g] = scale * (ds @ np.abs(k) + e * (p @ np.abs(k)))
+        a_dk += scale * (ds.T @ np.abs(q[:, g]) + p.T @ (e * np.abs(q[:, g])))
+        a_dv += p.T @ np.abs(do[:, g])
+    return a_o, a_dq, a_dk, a_dv
+
+
+def dump_report(path):
+    if not REPORT:
+        return
+    os.makedirs(os.path.dirname(path), exist_ok=True)
+    with open(path, "w") as f:
+        f.write(f"{'comparison':58s} {'max-abs':>10s} {'rel-Fro':>10s}\n")
+        for what, ma, rf in REPORT:
+            f.write(f"{what:58s} {ma:10.3e} {rf:10.3e}\n")

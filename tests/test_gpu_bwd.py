@@ -1,0 +1,116 @@
+"""GPU parity of the backward pass against the CPU fp64 oracle, through the C ABI.
+
+The GPU backward consumes the bf16 O and fp32 LSE written by the GPU forward (as the ABI
+requires); the oracle recomputes everything from q, k, v, dO in fp64."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2603_05451_amd import inputs as I
+from parity import assert_close, assert_close_terms, term_magnitudes
+
+pytestmark = pytest.mark.gpu
+
+
+def gpu_fwd_bwd(w, x):
+    import paper_2603_05451_amd as A
+    q, k, v, do = (x[n].cuda() for n in ("q", "k", "v", "do"))
+    o, lse = A.attn_fwd(q, k, v, w.scale, w.causal)
+    dq, dk, dv = A.attn_bwd(q, k, v, o, do, lse, w.scale, w.causal)
+    torch.cuda.synchronize()
+    return tuple(t.float().cpu().numpy() for t in (dq, dk, dv))
+
+
+SMALL = [
+    I.CANARY,
+    I.Workload("s_d64_c", 2, 4, 2, 384, 64, 64, True, 21),
+    I.Workload("s_d64_nc", 1, 3, 1, 256, 64, 64, False, 22),
+    I.Workload("s_d128_nc", 2, 4, 4, 384, 128, 128, False, 23),
+    I.Workload("s_d128_c", 2, 4, 2, 640, 128, 128, True, 24),
+    I.Workload("s_d192_c", 1, 4, 2, 384, 192, 128, True, 25),
+    I.Workload("s_d192_nc", 1, 2, 2, 256, 192, 128, False, 26),
+    I.Workload("s_d192_c_outl", 1, 2, 1, 512, 192, 128, True, 27, outlier_frac=0.01),
+]
+
+
+@pytest.mark.parametrize("w", SMALL, ids=lambda w: w.name)
+def test_bwd_small_full_parity(oracle, w):
+    x = I.make_inputs(w)
+    dq, dk, dv = gpu_fwd_bwd(w, x)
+    rdq, rdk, rdv = oracle.attn_bwd(*(I.to_f64(x[n]) for n in ("q", "k", "v", "do")), w.scale, w.causal)
+    if not w.outlier_frac:
+        assert_close(dq, rdq, f"dQ {w.name}")
+        assert_close(dk, rdk, f"dK {w.name}")
+        assert_close(dv, rdv, f"dV {w.name}")
+        return
+    G = w.H // w.Hkv
+    for b in range(w.B):
+        for kvh in range(w.Hkv):
+            hs = slice(kvh * G, (kvh + 1) * G)
+            _, a_dq, a_dk, a_dv = term_magnitudes(I.to_f64(x["q"][b, :, hs]), I.to_f64(x["k"][b, :, kvh]),
+                                                  I.to_f64(x["v"][b, :, kvh]), I.to_f64(x["do"][b, :, hs]),
+                                                  w.scale, w.causal)
+            assert_close_terms(dq[b, :, hs], rdq[b, :, hs], a_dq, f"dQ {w.name} b{b} kvh{kvh}")
+            assert_close_terms(dk[b, :, kvh], rdk[b, :, kvh], a_dk, f"dK {w.name} b{b} kvh{kvh}")
+            assert_close_terms(dv[b, :, kvh], rdv[b, :, kvh], a_dv, f"dV {w.name} b{b} kvh{kvh}")
+
+
+def test_bwd_run_to_run_difference_is_far_below_tolerance():
+    """dQ is summed with fp32 atomics in arbitrary order: results may differ in the last bits
+    only; dK and dV have a fixed order and must repeat exactly."""
+    w = I.Workload("rep", 1, 4, 2, 1024, 128, 128, True, 31)
+    x = I.make_inputs(w)
+    a = gpu_fwd_bwd(w, x)
+    b = gpu_fwd_bwd(w, x)
+    assert np.abs(a[0] - b[0]).max() <= 2e-3
+    assert np.array_equal(a[1], b[1]) and np.array_equal(a[2], b[2])
+
+
+FULL = [I.TARGET, I.SWEEP_D64_NC[0], I.SWEEP_D64_NC[5], I.SWEEP_D128_C[0], I.SWEEP_D128_C[4], I.GQA,
+        I.MLA_OUTLIER]
+
+
+@pytest.mark.parametrize("w", FULL, ids=lambda w: w.name)
+def test_bwd_full_size_sampled(oracle, w):
+    """Benchmark sizes.  dQ rows are row-separable: sampled rows against the oracle.  dK/dV of a
+    key need every query row that sees it: for causal workloads the last 256 keys only receive
+    gradient from the last 256 rows, which the oracle computes exactly; for non-causal ones the
+    oracle runs one full (batch, KV head) group when N <= 8192, else the check is the linear
+    identity sum_j dV_j = sum_i dO_i (rows of P sum to one) plus dQ rows."""
+    x = I.make_inputs(w)
+    dq, dk, dv = gpu_fwd_bwd(w, x)
+    for t in (dq, dk, dv):
+        assert np.isfinite(t).all()
+    rng = np.random.default_rng(w.seed)
+    rows = np.unique(np.concatenate([[0, 1, 63, 64, 127, 128, w.N - 65, w.N - 64, w.N - 1],
+                                     rng.integers(0, w.N, 24)]))
+    G = w.H // w.Hkv
+    b, kvh = w.B - 1, w.Hkv - 1
+    hs = slice(kvh * G, (kvh + 1) * G)
+    sl = lambda name, r: I.to_f64(x[name][b:b + 1, :, hs][:, r])
+    k = I.to_f64(x["k"][b:b + 1, :, kvh:kvh + 1])
+    v = I.to_f64(x["v"][b:b + 1, :, kvh:kvh + 1])
+    rdq, _, _ = oracle.attn_bwd(sl("q", rows), k, v, sl("do", rows), w.scale, w.causal, q_pos=rows)
+    if w.outlier_frac:
+        mags = lambda r: term_magnitudes(sl("q", r)[0], k[0, :, 0], v[0, :, 0], sl("do", r)[0], w.scale,
+                                         w.causal, q_pos=r)
+        cmp = lambda got, ref, mag, what: assert_close_terms(got, ref, mag, what)
+    else:
+        mags = lambda r: (None, None, None, None)
+        cmp = lambda got, ref, mag, what: assert_close(got, ref, what)
+    cmp(dq[b, :, hs][rows], rdq[0], mags(rows)[1], f"dQ rows {w.name}")
+    if w.causal:
+        tail = np.arange(w.N - 256, w.N)
+        _, rdk, rdv = oracle.attn_bwd(sl("q", tail), k, v, sl("do", tail), w.scale, True, q_pos=tail)
+        _, _, a_dk, a_dv = mags(tail)
+        cmp(dk[b, tail, kvh], rdk[0, tail, 0], None if a_dk is None else a_dk[tail], f"dK tail {w.name}")
+        cmp(dv[b, tail, kvh], rdv[0, tail, 0], None if a_dv is None else a_dv[tail], f"dV tail {w.name}")
+    elif w.N <= 8192:
+        allrows = np.arange(w.N)
+        _, rdk, rdv = oracle.attn_bwd(sl("q", allrows), k, v, sl("do", allrows), w.scale, False)
+        assert_close(dk[b:b + 1, :, kvh:kvh + 1], rdk, f"dK {w.name}")
+        assert_close(dv[b:b + 1, :, kvh:kvh + 1], rdv, f"dV {w.name}")
+    else:
+        want = I.to_f64(x["do"][b, :, hs]).sum(axis=(0, 1))
+        got = dv[b, :, kvh].astype(np.float64).sum(axis=0)
+        assert np.abs(got - want).max() <= 2e-2 * np.sqrt(w.N), "sum_j dV_j != sum_i dO_i"
