@@ -10,7 +10,7 @@
 //                 follows from the softmax Jacobian of Sec. 2.1), LSE in base-2 units, and
 //                 the fp32 dQ accumulator cleared.  HBM bound.
 //   bwd_main    : five MFMA contractions per (query tile, KV tile) pair.
-//   bwd_finish  : dq = bf16(scale * dq_acc).  HBM bound.
+//   bwd_finish  : dq = bf16(scale * dq_acc), from the head-major accumulator.  HBM bound.
 //
 // bwd_main layout.  Block = 4 waves = 128 keys (32 per wave); query tiles of 64 rows
 // stream through LDS (double buffered, direct global->LDS copies); this wave's K and V
@@ -72,19 +72,28 @@ bwd_prepare_kernel(const bf16* __restrict__ o, const bf16* __restrict__ d_o, con
 }
 
 // ------------------------------------------------------------------------------------------
+// bwd_finish: dq[b, i, h, :] = bf16(scale * dq_acc[b, h, i, :]); one thread per 8 elements.
 template <int DQK>
 __global__ void __launch_bounds__(256)
-bwd_finish_kernel(const float* __restrict__ dq_acc, bf16* __restrict__ dq, float scale, int64_t n8)
+bwd_finish_kernel(const float* __restrict__ dq_acc, bf16* __restrict__ dq, float scale, int H, int N, int64_t n8)
 {
-    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;   // group of 8 elements
-    if (i >= n8) return;
-    const float4 a = ((const float4*)dq_acc)[2 * i], b = ((const float4*)dq_acc)[2 * i + 1];
+    constexpr int CPR = DQK / 8;
+    const int64_t t = (int64_t)blockIdx.x * 256 + threadIdx.x;   // output chunk index, token-major
+    if (t >= n8) return;
+    const int ch = (int)(t % CPR);
+    const int64_t row = t / CPR;                                  // (b*N + i)*H + h
+    const int64_t bi = row / H;
+    const int h = (int)(row - bi * H);
+    const int64_t b = bi / N;
+    const int i = (int)(bi - b * N);
+    const float4* src = (const float4*)(dq_acc + (((b * H + h) * N + i) * DQK + ch * 8));
+    const float4 x = src[0], y = src[1];
     bf16x8 out;
-    out[0] = (bf16)(a.x * scale); out[1] = (bf16)(a.y * scale);
-    out[2] = (bf16)(a.z * scale); out[3] = (bf16)(a.w * scale);
-    out[4] = (bf16)(b.x * scale); out[5] = (bf16)(b.y * scale);
-    out[6] = (bf16)(b.z * scale); out[7] = (bf16)(b.w * scale);
-    ((bf16x8*)dq)[i] = out;
+    out[0] = (bf16)(x.x * scale); out[1] = (bf16)(x.y * scale);
+    out[2] = (bf16)(x.z * scale); out[3] = (bf16)(x.w * scale);
+    out[4] = (bf16)(y.x * scale); out[5] = (bf16)(y.y * scale);
+    out[6] = (bf16)(y.z * scale); out[7] = (bf16)(y.w * scale);
+    ((bf16x8*)dq)[t] = out;
 }
 
 // ------------------------------------------------------------------------------------------
@@ -151,7 +160,7 @@ attn_bwd_kernel(const bf16* __restrict__ q, const bf16* __restrict__ k, const bf
         tile_load_async<BWD_BQ, DV, BWD_NT>(d_o + row0 * o_stride + (int64_t)hq * DV, o_stride, do_lds[buf], tid);
         if (wave < 2) {   // 64 floats each of lse2 and D
             const float* src = (wave == 0 ? lse2 : D) + ((int64_t)b * H + hq) * N + (int64_t)i * BWD_BQ + lane;
-            __builtin_amdgcn_global_load_lds((const void*)src, (ATTN_LDS void*)(st_lds + buf * 512 + wave * 256), 4, 0, 0);
+            dma4(src, st_lds + buf * 512 + wave * 256);
         }
     };
 
@@ -168,6 +177,10 @@ attn_bwd_kernel(const bf16* __restrict__ q, const bf16* __restrict__ k, const bf
         for (int ks = 0; ks < KSQ; ++ks) kf[ks] = *(const bf16x8*)(krow + 16 * ks);
 #pragma unroll
         for (int ks = 0; ks < KSV; ++ks) vf[ks] = *(const bf16x8*)(vrow + 16 * ks);
+#pragma unroll
+        for (int ks = 0; ks < KSQ; ++ks) pin_ready(kf[ks]);
+#pragma unroll
+        for (int ks = 0; ks < KSV; ++ks) pin_ready(vf[ks]);
     }
 
     f32x16 dk_acc[DBQ], dv_acc[DBV];
@@ -180,11 +193,25 @@ attn_bwd_kernel(const bf16* __restrict__ q, const bf16* __restrict__ k, const bf
 #pragma unroll
         for (int r = 0; r < 16; ++r) dv_acc[db][r] = 0.f;
 
+    // dQ blocks of the previous step.  Their atomic adds are issued one step late, right after
+    // the top-of-step wait, so that they drain underneath a whole step of MFMA work instead of
+    // being waited for by the next vmcnt(0).
+    f32x16 dq_blk[NDQ];
+    float* dq_dst = nullptr;
+    auto flush_dq = [&]() {
+#pragma unroll
+        for (int n = 0; n < NDQ; ++n)
+#pragma unroll
+            for (int r = 0; r < 16; ++r)
+                unsafeAtomicAdd(dq_dst + acc_row(r, h) * DQK + 64 * n, dq_blk[n][r]);
+    };
+
     for (int step = 0; step < nsteps; ++step) {
         const int buf = step & 1;
         wait_async_copies();
         __syncthreads();           // tiles of this step visible; previous step's dS reads finished
         if (step + 1 < nsteps) issue_loads(step + 1, buf ^ 1);
+        if (step > 0) flush_dq();
 
         const int g = step / nq, i = i_first + (step - g * nq);
         const int hq = kvh * G + g;
@@ -194,16 +221,59 @@ attn_bwd_kernel(const bf16* __restrict__ q, const bf16* __restrict__ k, const bf
         bf16x8 pb[QB][2], dsb[QB][2];
 #pragma unroll
         for (int qb = 0; qb < QB; ++qb) {
-            // ---- S = Q K_w^T and dP = dO V_w^T for 32 queries x 32 keys
+            // ---- S = Q K_w^T and dP = dO V_w^T for 32 queries x 32 keys; LDS reads run one
+            // group of 4 fragments ahead of the MFMAs that consume them
             f32x16 s, dp;
 #pragma unroll
             for (int r = 0; r < 16; ++r) { s[r] = 0.f; dp[r] = 0.f; }
+            {
+                constexpr int GRP = 4, NS = KSQ + KSV, NG = NS / GRP;
+                static_assert(KSQ % GRP == 0 && KSV % GRP == 0, "k-steps must split into whole groups");
+                bf16x8 fr[2][GRP];
+                auto load_a = [&](int g, bf16x8* dst) {
 #pragma unroll
-            for (int ks = 0; ks < KSQ; ++ks)
-                s = mfma32(lds_read_b128(q_lds[buf] + tile_off<DQK>(32 * qb + c, 2 * ks + h)), kf[ks], s);
+                    for (int t = 0; t < GRP; ++t) {
+                        const int st = g * GRP + t;
+                        dst[t] = st < KSQ
+                            ? lds_read_b128(q_lds[buf] + tile_off<DQK>(32 * qb + c, 2 * st + h))
+                            : lds_read_b128(do_lds[buf] + tile_off<DV>(32 * qb + c, 2 * (st - KSQ) + h));
+                    }
+                };
+                load_a(0, fr[0]);
 #pragma unroll
-            for (int ks = 0; ks < KSV; ++ks)
-                dp = mfma32(lds_read_b128(do_lds[buf] + tile_off<DV>(32 * qb + c, 2 * ks + h)), vf[ks], dp);
+                for (int g = 0; g < NG; ++g) {
+                    if (g + 1 < NG) load_a(g + 1, fr[(g + 1) & 1]);
+                    sched_fence();
+#pragma unroll
+                    for (int t = 0; t < GRP; ++t) {
+                        const int st = g * GRP + t;
+                        if (st < KSQ) s = mfma32(fr[g & 1][t], kf[st], s);
+                        else dp = mfma32(fr[g & 1][t], vf[st - KSQ], dp);
+                    }
+                    sched_fence();
+                }
+            }
+
+            // transposed fragments of dO and Q for the first 16 queries: in flight during the
+            // elementwise work below
+            bf16x4 tfr[2][DBV + DBQ][2];
+            auto load_t = [&](int kk, bf16x4 (*dst)[2]) {
+                const int row_lo = 32 * qb + 16 * kk + 4 * h + tr_row;   // queries, order 8s + 4h + j
+#pragma unroll
+                for (int db = 0; db < DBV; ++db) {
+                    const ATTN_LDS char* base = do_lds[buf] + tr_half;
+                    dst[db][0] = lds_read_tr(base + tile_off<DV>(row_lo, 4 * db + tr_chunk));
+                    dst[db][1] = lds_read_tr(base + tile_off<DV>(row_lo + 8, 4 * db + tr_chunk));
+                }
+#pragma unroll
+                for (int db = 0; db < DBQ; ++db) {
+                    const ATTN_LDS char* base = q_lds[buf] + tr_half;
+                    dst[DBV + db][0] = lds_read_tr(base + tile_off<DQK>(row_lo, 4 * db + tr_chunk));
+                    dst[DBV + db][1] = lds_read_tr(base + tile_off<DQK>(row_lo + 8, 4 * db + tr_chunk));
+                }
+            };
+            load_t(0, tfr[0]);
+            sched_fence();
 
             // ---- P = 2^(c S - LSE2), dS = P o (dP - D); the query index is the register row
             const ATTN_LDS float* st = (const ATTN_LDS float*)(st_lds + buf * 512);
@@ -234,21 +304,16 @@ attn_bwd_kernel(const bf16* __restrict__ q, const bf16* __restrict__ k, const bf
             // ---- dV_w^T += dO^T P,  dK_w^T += Q^T dS   (contraction over these 32 queries)
 #pragma unroll
             for (int kk = 0; kk < 2; ++kk) {
-                const int row_lo = 32 * qb + 16 * kk + 4 * h + tr_row;   // queries, order 8s + 4h + j
+                if (kk + 1 < 2) load_t(kk + 1, tfr[(kk + 1) & 1]);
+                sched_fence();
 #pragma unroll
-                for (int db = 0; db < DBV; ++db) {
-                    const ATTN_LDS char* base = do_lds[buf] + tr_half;
-                    bf16x4 lo = lds_read_tr(base + tile_off<DV>(row_lo, 4 * db + tr_chunk));
-                    bf16x4 hi = lds_read_tr(base + tile_off<DV>(row_lo + 8, 4 * db + tr_chunk));
-                    dv_acc[db] = mfma32(cat4(lo, hi), pb[qb][kk], dv_acc[db]);
-                }
+                for (int db = 0; db < DBV; ++db)
+                    dv_acc[db] = mfma32(cat4(tfr[kk & 1][db][0], tfr[kk & 1][db][1]), pb[qb][kk], dv_acc[db]);
 #pragma unroll
-                for (int db = 0; db < DBQ; ++db) {
-                    const ATTN_LDS char* base = q_lds[buf] + tr_half;
-                    bf16x4 lo = lds_read_tr(base + tile_off<DQK>(row_lo, 4 * db + tr_chunk));
-                    bf16x4 hi = lds_read_tr(base + tile_off<DQK>(row_lo + 8, 4 * db + tr_chunk));
-                    dk_acc[db] = mfma32(cat4(lo, hi), dsb[qb][kk], dk_acc[db]);
-                }
+                for (int db = 0; db < DBQ; ++db)
+                    dk_acc[db] = mfma32(cat4(tfr[kk & 1][DBV + db][0], tfr[kk & 1][DBV + db][1]), dsb[qb][kk],
+                                        dk_acc[db]);
+                sched_fence();
             }
         }
 
@@ -257,37 +322,42 @@ attn_bwd_kernel(const bf16* __restrict__ q, const bf16* __restrict__ k, const bf
         // ---- dQ blocks: (32 queries) x (32 dims), contraction over the block's 128 keys
         {
             const int qb = wave & 1;
-            f32x16 dq_blk[NDQ];
+            constexpr int NKS = BWD_BK / 16;
 #pragma unroll
             for (int n = 0; n < NDQ; ++n)
 #pragma unroll
                 for (int r = 0; r < 16; ++r) dq_blk[n][r] = 0.f;
-#pragma unroll
-            for (int ks = 0; ks < BWD_BK / 16; ++ks) {
+            bf16x4 fr[2][1 + NDQ][2];
+            auto load_dq = [&](int ks, bf16x4 (*dst)[2]) {
                 const int row_lo = 16 * ks + 8 * h + tr_row;             // keys, natural order 8h + 4s + j
                 const ATTN_LDS char* abase = ds_lds + tr_half;
-                bf16x4 alo = lds_read_tr(abase + tile_off<BWD_BQ>(row_lo, 4 * qb + tr_chunk));
-                bf16x4 ahi = lds_read_tr(abase + tile_off<BWD_BQ>(row_lo + 4, 4 * qb + tr_chunk));
-                const bf16x8 a = cat4(alo, ahi);
+                dst[0][0] = lds_read_tr(abase + tile_off<BWD_BQ>(row_lo, 4 * qb + tr_chunk));
+                dst[0][1] = lds_read_tr(abase + tile_off<BWD_BQ>(row_lo + 4, 4 * qb + tr_chunk));
 #pragma unroll
                 for (int n = 0; n < NDQ; ++n) {
                     const int db = (wave >> 1) + 2 * n;
                     const ATTN_LDS char* bbase = k_lds + tr_half;
-                    bf16x4 blo = lds_read_tr(bbase + tile_off<DQK>(row_lo, 4 * db + tr_chunk));
-                    bf16x4 bhi = lds_read_tr(bbase + tile_off<DQK>(row_lo + 4, 4 * db + tr_chunk));
-                    dq_blk[n] = mfma32(a, cat4(blo, bhi), dq_blk[n]);
+                    dst[1 + n][0] = lds_read_tr(bbase + tile_off<DQK>(row_lo, 4 * db + tr_chunk));
+                    dst[1 + n][1] = lds_read_tr(bbase + tile_off<DQK>(row_lo + 4, 4 * db + tr_chunk));
                 }
-            }
+            };
+            load_dq(0, fr[0]);
 #pragma unroll
-            for (int n = 0; n < NDQ; ++n) {
-                const int db = (wave >> 1) + 2 * n;
-                float* dst = dq_acc + ((int64_t)b * N + q0 + 32 * qb) * q_stride + (int64_t)hq * DQK + 32 * db + c;
+            for (int ks = 0; ks < NKS; ++ks) {
+                if (ks + 1 < NKS) load_dq(ks + 1, fr[(ks + 1) & 1]);
+                sched_fence();
+                const bf16x8 a = cat4(fr[ks & 1][0][0], fr[ks & 1][0][1]);
 #pragma unroll
-                for (int r = 0; r < 16; ++r)
-                    unsafeAtomicAdd(dst + (int64_t)acc_row(r, h) * q_stride, dq_blk[n][r]);
+                for (int n = 0; n < NDQ; ++n)
+                    dq_blk[n] = mfma32(a, cat4(fr[ks & 1][1 + n][0], fr[ks & 1][1 + n][1]), dq_blk[n]);
+                sched_fence();
             }
+            // accumulator is head-major [B, H, N, d_qk]: a dQ tile is one contiguous region;
+            // block n of this wave covers dims 32 * (wave/2 + 2n) .. +31
+            dq_dst = dq_acc + (((int64_t)b * H + hq) * N + q0 + 32 * qb) * DQK + 32 * (wave >> 1) + c;
         }
     }
+    if (nsteps > 0) flush_dq();
 
     // ---- epilogue: dk = scale * dK, dv = dV; accumulators hold the transposes (dims x keys)
     bf16* dkrow = dk + ((int64_t)b * N + kw0 + c) * k_stride + (int64_t)kvh * DQK;
@@ -343,7 +413,7 @@ static int launch_bwd_t(const BwdArgs& a)
     if (a.phases & 4) {
         const int64_t n8 = nrows * DQK / 8;
         if (launch_kernel(bwd_finish_kernel<DQK>, dim3((unsigned)((n8 + 255) / 256)), dim3(256), 0, st,
-                          (const float*)a.dq_acc, (bf16*)a.dq, a.scale, n8) != hipSuccess)
+                          (const float*)a.dq_acc, (bf16*)a.dq, a.scale, a.H, a.N, n8) != hipSuccess)
             return -3;
     }
     return 0;

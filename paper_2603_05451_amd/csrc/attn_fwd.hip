@@ -81,6 +81,8 @@ attn_fwd_kernel(const bf16* __restrict__ q, const bf16* __restrict__ k, const bf
         const bf16* qrow = q + ((int64_t)b * N + qw0 + c) * q_stride + (int64_t)hq * DQK + 8 * h;
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) qf[ks] = *(const bf16x8*)(qrow + 16 * ks);
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) pin_ready(qf[ks]);
     }
 
     f32x16 oacc[DB];
@@ -112,18 +114,50 @@ attn_fwd_kernel(const bf16* __restrict__ q, const bf16* __restrict__ k, const bf
         const int key0 = j * FWD_BN;
         if (CAUSAL && key0 > qw0 + 31) continue;   // whole tile above this wave's diagonal
 
-        // ---- S^T = K Q^T : KB blocks of 32 keys x 32 queries
+        // ---- S^T = K Q^T : KB blocks of 32 keys x 32 queries.  LDS reads run one group of
+        // GRP fragments ahead of the MFMAs that consume them.
         f32x16 s[KB];
 #pragma unroll
-        for (int kb = 0; kb < KB; ++kb) {
+        for (int kb = 0; kb < KB; ++kb)
 #pragma unroll
             for (int r = 0; r < 16; ++r) s[kb][r] = 0.f;
+        {
+            constexpr int GRP = 4, NG = KB * KS / GRP;
+            static_assert(KB * KS % GRP == 0, "k-steps must split into whole groups");
+            bf16x8 kfr[2][GRP];
+            auto load_k = [&](int g, bf16x8* dst) {
 #pragma unroll
-            for (int ks = 0; ks < KS; ++ks) {
-                bf16x8 kf = lds_read_b128(k_lds[buf] + tile_off<DQK>(32 * kb + c, 2 * ks + h));
-                s[kb] = mfma32(kf, qf[ks], s[kb]);
+                for (int t = 0; t < GRP; ++t) {
+                    const int st = g * GRP + t, kb = st / KS, ks = st % KS;
+                    dst[t] = lds_read_b128(k_lds[buf] + tile_off<DQK>(32 * kb + c, 2 * ks + h));
+                }
+            };
+            load_k(0, kfr[0]);
+#pragma unroll
+            for (int g = 0; g < NG; ++g) {
+                if (g + 1 < NG) load_k(g + 1, kfr[(g + 1) & 1]);
+                sched_fence();
+#pragma unroll
+                for (int t = 0; t < GRP; ++t) {
+                    const int st = g * GRP + t, kb = st / KS, ks = st % KS;
+                    s[kb] = mfma32(kfr[g & 1][t], qf[ks], s[kb]);
+                }
+                sched_fence();
             }
         }
+
+        // first group of V^T fragments: in flight during the softmax arithmetic
+        bf16x4 vfr[2][DB][2];
+        auto load_v = [&](int kk, bf16x4 (*dst)[2]) {
+            const ATTN_LDS char* base = v_lds[buf] + v_half;
+#pragma unroll
+            for (int db = 0; db < DB; ++db) {
+                dst[db][0] = lds_read_tr(base + tile_off<DV>(16 * kk + v_row0, 4 * db + v_chunk0));
+                dst[db][1] = lds_read_tr(base + tile_off<DV>(16 * kk + 8 + v_row0, 4 * db + v_chunk0));
+            }
+        };
+        load_v(0, vfr[0]);
+        sched_fence();
 
         // ---- causal mask on tiles that straddle the diagonal
         if (CAUSAL && key0 + FWD_BN - 1 > qw0) {
@@ -167,13 +201,12 @@ attn_fwd_kernel(const bf16* __restrict__ q, const bf16* __restrict__ k, const bf
         // ---- O^T += V^T P^T : contraction over the 64 keys in 4 steps of 16
 #pragma unroll
         for (int kk = 0; kk < 2 * KB; ++kk) {
+            if (kk + 1 < 2 * KB) load_v(kk + 1, vfr[(kk + 1) & 1]);
+            sched_fence();
 #pragma unroll
-            for (int db = 0; db < DB; ++db) {
-                const ATTN_LDS char* base = v_lds[buf] + v_half;
-                bf16x4 lo = lds_read_tr(base + tile_off<DV>(16 * kk + v_row0, 4 * db + v_chunk0));
-                bf16x4 hi = lds_read_tr(base + tile_off<DV>(16 * kk + 8 + v_row0, 4 * db + v_chunk0));
-                oacc[db] = mfma32(cat4(lo, hi), pf[kk >> 1][kk & 1], oacc[db]);
-            }
+            for (int db = 0; db < DB; ++db)
+                oacc[db] = mfma32(cat4(vfr[kk & 1][db][0], vfr[kk & 1][db][1]), pf[kk >> 1][kk & 1], oacc[db]);
+            sched_fence();
         }
     }
 

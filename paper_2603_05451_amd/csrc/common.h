@@ -90,10 +90,29 @@ __device__ __forceinline__ int tile_off(int row, int chunk)
     return (row * (D / 8) + swz_chunk<D>(row, chunk)) * 16;
 }
 
+// One wave instruction of the global->LDS DMA: every lane copies 16 bytes from its own global
+// address to LDS address (lds_base + 16 * lane); lds_base must be wave-uniform (it travels in
+// M0).  Issued through inline assembly on purpose: the compiler then does not know that LDS is
+// being written asynchronously and inserts no vmcnt waits of its own in front of later LDS
+// reads; the kernels order the copy explicitly (wait_async_copies + workgroup barrier).
+// vmcnt operations the compiler cannot see only ever make its own waits stricter.
+__device__ __forceinline__ void dma16(const void* gsrc, ATTN_LDS char* lds_base)
+{
+    const uint32_t m0 = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)lds_base);
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off"
+                 :: "s"(m0), "v"(gsrc) : "memory");
+}
+__device__ __forceinline__ void dma4(const void* gsrc, ATTN_LDS char* lds_base)   // 4 bytes per lane
+{
+    const uint32_t m0 = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)lds_base);
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dword %1, off"
+                 :: "s"(m0), "v"(gsrc) : "memory");
+}
+
 // Asynchronous copy of a ROWS x D bf16 tile from global memory (row stride `gstride`
 // elements) into an LDS tile, by all NT threads of the block.  No VGPR staging: each
 // wave instruction moves 64 x 16 bytes straight into LDS.  Completion is observed with
-// s_waitcnt vmcnt(0) followed by a workgroup barrier.
+// wait_async_copies() followed by a workgroup barrier.
 template <int ROWS, int D, int NT>
 __device__ __forceinline__ void tile_load_async(const bf16* __restrict__ g, int64_t gstride,
                                                 ATTN_LDS char* lds, int tid)
@@ -108,12 +127,21 @@ __device__ __forceinline__ void tile_load_async(const bf16* __restrict__ g, int6
         const int p = p0 + lane;
         const int row = p / CPR;
         const int chunk = swz_chunk<D>(row, p % CPR);   // XOR is its own inverse
-        const bf16* src = g + (int64_t)row * gstride + chunk * 8;
-        __builtin_amdgcn_global_load_lds((const void*)src, (ATTN_LDS void*)(lds + p0 * 16), 16, 0, 0);
+        dma16(g + (int64_t)row * gstride + chunk * 8, lds + p0 * 16);
     }
 }
 
 __device__ __forceinline__ void wait_async_copies() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+
+// Make the compiler treat a register value as produced here: any wait for the load that fed
+// it is placed before this point (used to keep vmcnt waits for one-off global loads out of
+// loops that have DMA copies in flight).
+template <typename T>
+__device__ __forceinline__ void pin_ready(T& x) { asm volatile("" : "+v"(x)); }
+
+// Scheduling fence: memory and MFMA instructions stay on their side, plain VALU/SALU/
+// transcendental work may move across (so softmax arithmetic can fill MFMA shadows).
+__device__ __forceinline__ void sched_fence() { __builtin_amdgcn_sched_barrier(0x2 | 0x4 | 0x400); }
 
 __device__ __forceinline__ bf16x8 lds_read_b128(const ATTN_LDS char* p)
 {
