@@ -34,7 +34,7 @@ def event_ms(fn, n):
     return e0.elapsed_time(e1) / n
 
 
-def cpu_baseline(w, x, seconds_target=15.0):
+def cpu_baseline(w, x, seconds_target=8.0):
     """The fp64 oracle as it stands, timed on this machine's host cores, on a bounded sample of the
     same workload: a contiguous block of query rows of (batch 0, head 0) against all N keys,
     forward + backward.  FLOPs by the same convention as the GPU figure."""
@@ -120,12 +120,15 @@ def main():
     ms_fwd = event_ms(fwd, n)
     ms_bwd = event_ms(bwd, n)
     ms_prep = event_ms(lambda: bwd(A.ATTN_BWD_PREPARE), n)
-    ms_main = event_ms(lambda: bwd(A.ATTN_BWD_MAIN), n)
-    ms_fin = event_ms(lambda: bwd(A.ATTN_BWD_FINISH), n)
+    ms_dkdv = event_ms(lambda: bwd(A.ATTN_BWD_DKDV), n)
+    ms_dq = event_ms(lambda: bwd(A.ATTN_BWD_DQ), n)
     bwd()                                    # leave consistent outputs behind
     torch.cuda.synchronize()
 
     f_fwd, f_bwd = w.fwd_flops(), w.bwd_flops()
+    pairs = w.B * w.H * float(w.N) * w.N * (0.5 if w.causal else 1.0)       # (query, key) pairs
+    f_dkdv = 2.0 * pairs * (2 * w.dqk + 2 * w.dv)     # S, dK contract/emit d_qk; dP, dV d_v
+    f_dq = 2.0 * pairs * (2 * w.dqk + w.dv)           # S, dQ over d_qk; dP over d_v
     tf = lambda flops, ms: flops / ms / 1e9
     out = {
         "metric": "attention fwd / bwd TFLOPs/s (bf16) and % of MI355X dense BF16 MFMA peak",
@@ -140,11 +143,15 @@ def main():
                 "frac_of_peak": round(tf(f_fwd, ms_fwd) / PEAK_BF16_TFLOPS, 4)},
         "bwd": {"ms": round(ms_bwd, 4), "tflops": round(tf(f_bwd, ms_bwd), 1),
                 "frac_of_peak": round(tf(f_bwd, ms_bwd) / PEAK_BF16_TFLOPS, 4),
-                "ms_prepare": round(ms_prep, 4), "ms_main": round(ms_main, 4), "ms_finish": round(ms_fin, 4)},
-        # dominant kernel = backward main kernel: 5 contractions of 2 N^2 d each per head and batch
-        "roofline": {"kernel": "attn_bwd_kernel", "bound": "mfma", "achieved": round(tf(f_bwd, ms_main), 1),
-                     "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                     "frac": round(tf(f_bwd, ms_main) / PEAK_BF16_TFLOPS, 4), "traffic": None},
+                "ms_prepare": round(ms_prep, 4), "ms_dkdv": round(ms_dkdv, 4), "ms_dq": round(ms_dq, 4)},
+        # dominant kernel = attn_bwd_dkdv_kernel.  Its ALGORITHMIC work is what it executes on the
+        # MFMA units: four contractions (S, dP, dV, dK) of N^2 (d_qk or d_v) multiply-adds each.
+        "roofline": {"kernel": "attn_bwd_dkdv_kernel", "bound": "mfma",
+                     "achieved": round(tf(f_dkdv, ms_dkdv), 1), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                     "frac": round(tf(f_dkdv, ms_dkdv) / PEAK_BF16_TFLOPS, 4), "traffic": None},
+        "roofline_dq": {"kernel": "attn_bwd_dq_kernel", "bound": "mfma",
+                        "achieved": round(tf(f_dq, ms_dq), 1), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                        "frac": round(tf(f_dq, ms_dq) / PEAK_BF16_TFLOPS, 4), "traffic": None},
         "roofline_fwd": {"kernel": "attn_fwd_kernel", "bound": "mfma", "achieved": round(tf(f_fwd, ms_fwd), 1),
                          "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                          "frac": round(tf(f_fwd, ms_fwd) / PEAK_BF16_TFLOPS, 4), "traffic": None},

@@ -59,19 +59,21 @@ int attn_fwd_ex(const void* q, const void* k, const void* v, void* o, float* lse
                 int B, int H, int Hkv, int N, int d_qk, int d_v, float scale, int causal,
                 void* stream);
 
-/* Backward pass (paper Sec. 2.1 second display; loop structure per Sec. 3.2.2:
- * one workgroup per KV tile, dK/dV accumulated on chip, dQ accumulated across KV
- * tiles in fp32 in the workspace and converted at the end).
+/* Backward pass (paper Sec. 2.1 second display).
  *   in : q, k, v as above; o, d_o [B,N,H,d_v] bf16; lse [B,H,N] fp32 -- o and lse
  *        must be the outputs of the forward call with the same arguments
  *   out: dq [B,N,H,d_qk], dk [B,N,Hkv,d_qk], dv [B,N,Hkv,d_v]  bf16
  *   workspace: device scratch of at least attn_bwd_workspace_bytes(...) bytes,
  *        256-byte aligned; contents on entry are ignored, contents on exit are
  *        unspecified; may be reused by the next call on the same stream.
- * Three kernels are enqueued: D = rowsum(dO o O) (which also clears the fp32 dQ
- * accumulator), the main kernel, and the dQ conversion.  dQ is summed with fp32
- * atomics, so its low-order bits can differ from run to run (paper Sec. 3.2.4
- * names the same property). */
+ * Three kernels are enqueued: D = rowsum(dO o O) with the base-2 LSE; the dK/dV kernel
+ * (one workgroup per KV tile, dK and dV accumulated on chip over all query tiles and all
+ * query heads of the group: the loop structure of paper Sec. 3.2.2); and the dQ kernel
+ * (one workgroup per query tile, dQ accumulated on chip over all KV tiles).  The paper
+ * accumulates dQ with global atomics inside the dK/dV loop (Sec. 3.2.2-3.2.3); on MI355X
+ * those atomics are memory-side and cost more than recomputing S and dP, so dQ has its
+ * own pass.  No atomics are used: results are bit-reproducible from run to run (the
+ * property paper Sec. 3.2.4 obtains with semaphores). */
 int attn_bwd(const void* q, const void* k, const void* v, const void* o, const void* d_o,
              const float* lse, void* dq, void* dk, void* dv,
              int B, int H, int Hkv, int N, int d, float scale, int causal,
@@ -83,19 +85,18 @@ int attn_bwd_ex(const void* q, const void* k, const void* v, const void* o, cons
 
 /* attn_bwd_ex restricted to a subset of its three kernels, for per-kernel timing and
  * profiling (the backward of paper Sec. 3.2 is one logical step; this splits it at the
- * kernel boundaries).  phases is a bit mask: ATTN_BWD_PREPARE (D, base-2 LSE, clear the dQ
- * accumulator), ATTN_BWD_MAIN (dK, dV, dQ accumulation), ATTN_BWD_FINISH (dq from the
- * accumulator).  All arguments as attn_bwd_ex.  Running the three phases in order on one
- * stream with the same workspace is exactly attn_bwd_ex; running ATTN_BWD_MAIN repeatedly
- * without ATTN_BWD_PREPARE keeps adding to the accumulator (timing use only). */
-enum { ATTN_BWD_PREPARE = 1, ATTN_BWD_MAIN = 2, ATTN_BWD_FINISH = 4, ATTN_BWD_ALL = 7 };
+ * kernel boundaries).  phases is a bit mask: ATTN_BWD_PREPARE (D and base-2 LSE into the
+ * workspace), ATTN_BWD_DKDV (writes dk, dv), ATTN_BWD_DQ (writes dq).  All arguments as
+ * attn_bwd_ex.  ATTN_BWD_DKDV and ATTN_BWD_DQ read what ATTN_BWD_PREPARE left in the
+ * workspace and are independent of each other. */
+enum { ATTN_BWD_PREPARE = 1, ATTN_BWD_DKDV = 2, ATTN_BWD_DQ = 4, ATTN_BWD_ALL = 7 };
 int attn_bwd_phases(const void* q, const void* k, const void* v, const void* o, const void* d_o,
                     const float* lse, void* dq, void* dk, void* dv,
                     int B, int H, int Hkv, int N, int d_qk, int d_v, float scale, int causal,
                     void* workspace, size_t workspace_bytes, void* stream, int phases);
 
 /* Bytes of workspace attn_bwd(_ex) needs for these sizes (0 if they are invalid):
- * the fp32 dQ accumulator [B,N,H,d_qk] plus D and the base-2 LSE, [B,H,N] fp32 each. */
+ * D and the base-2 LSE, [B,H,N] fp32 each (256-byte aligned sections). */
 size_t attn_bwd_workspace_bytes(int B, int H, int Hkv, int N, int d_qk, int d_v);
 
 /* Human-readable text for a return code (static storage). */

@@ -107,7 +107,7 @@ def attn_fwd(q, k, v, scale, causal, o=None, lse=None, stream=None):
     return o, lse
 
 
-ATTN_BWD_PREPARE, ATTN_BWD_MAIN, ATTN_BWD_FINISH, ATTN_BWD_ALL = 1, 2, 4, 7
+ATTN_BWD_PREPARE, ATTN_BWD_DKDV, ATTN_BWD_DQ, ATTN_BWD_ALL = 1, 2, 4, 7
 
 
 def attn_bwd(q, k, v, o, do, lse, scale, causal, dq=None, dk=None, dv=None, workspace=None,

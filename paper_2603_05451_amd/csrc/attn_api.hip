@@ -28,15 +28,14 @@ int check_sizes(int B, int H, int Hkv, int N, int d_qk, int d_v)
 size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
 struct WorkspaceLayout {
-    size_t dq_acc_off, d_off, lse2_off, total;
+    size_t d_off, lse2_off, total;
 };
 
-WorkspaceLayout workspace_layout(int B, int H, int N, int d_qk)
+WorkspaceLayout workspace_layout(int B, int H, int N)
 {
     WorkspaceLayout w;
     const size_t rows = (size_t)B * H * N;
-    w.dq_acc_off = 0;
-    w.d_off = align_up(rows * (size_t)d_qk * sizeof(float), 256);
+    w.d_off = 0;
     w.lse2_off = w.d_off + align_up(rows * sizeof(float), 256);
     w.total = w.lse2_off + align_up(rows * sizeof(float), 256);
     return w;
@@ -70,7 +69,7 @@ int attn_fwd(const void* q, const void* k, const void* v, void* o, float* lse,
 size_t attn_bwd_workspace_bytes(int B, int H, int Hkv, int N, int d_qk, int d_v)
 {
     if (check_sizes(B, H, Hkv, N, d_qk, d_v) != ATTN_OK) return 0;
-    return workspace_layout(B, H, N, d_qk).total;
+    return workspace_layout(B, H, N).total;
 }
 
 int attn_bwd_phases(const void* q, const void* k, const void* v, const void* o, const void* d_o,
@@ -86,11 +85,10 @@ int attn_bwd_phases(const void* q, const void* k, const void* v, const void* o, 
     for (const void* p : ptrs)
         if (misaligned(p, 16)) return ATTN_EINVAL;
     if (misaligned(lse, 4) || misaligned(workspace, 256)) return ATTN_EINVAL;
-    const WorkspaceLayout w = workspace_layout(B, H, N, d_qk);
+    const WorkspaceLayout w = workspace_layout(B, H, N);
     if (workspace_bytes < w.total) return ATTN_EINVAL;
     char* ws = static_cast<char*>(workspace);
     attn::BwdArgs a{q, k, v, o, d_o, lse, dq, dk, dv, B, H, Hkv, N, d_qk, d_v, scale, causal != 0,
-                    reinterpret_cast<float*>(ws + w.dq_acc_off),
                     reinterpret_cast<float*>(ws + w.d_off),
                     reinterpret_cast<float*>(ws + w.lse2_off), stream, phases};
     const int rc = attn::launch_bwd(a);

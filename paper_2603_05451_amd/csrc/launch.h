@@ -23,12 +23,11 @@ struct BwdArgs {
     int B, H, Hkv, N, d_qk, d_v;
     float scale;
     int causal;
-    // workspace carved up by the API: fp32 dQ accumulator, D = rowsum(dO o O), base-2 LSE
-    float* dq_acc;
+    // workspace carved up by the API: D = rowsum(dO o O) and the base-2 LSE
     float* D;
     float* lse2;
     void* stream;
-    int phases;   // bit mask: 1 prepare, 2 main, 4 finish
+    int phases;   // bit mask: 1 prepare, 2 dK/dV kernel, 4 dQ kernel
 };
 
 // Launch through hipLaunchKernel so that the status returned belongs to THIS launch (the

@@ -1,0 +1,97 @@
+"""CPU-only checks of the C ABI: the library loads, exports every function include/attn.h
+declares, and rejects bad arguments before touching the GPU."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def L():
+    import paper_2603_05451_amd as A
+    if not os.path.exists(A.LIB_PATH):
+        from paper_2603_05451_amd import build
+        build.build_library()
+    return A.lib()
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "attn.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(attn_[a-z_]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported(L):
+    names = declared_functions()
+    assert {"attn_fwd", "attn_fwd_ex", "attn_bwd", "attn_bwd_ex", "attn_bwd_phases",
+            "attn_bwd_workspace_bytes", "attn_strerror", "attn_version"} <= set(names)
+    for n in names:
+        assert hasattr(L, n), f"libattn.so does not export {n}"
+
+
+def test_version_and_error_strings(L):
+    import paper_2603_05451_amd as A
+    assert A.attn_version() >= 100
+    for code in (0, -1, -2, -3, -99):
+        assert isinstance(A.attn_strerror(code), str) and A.attn_strerror(code)
+
+
+def test_workspace_size(L):
+    import paper_2603_05451_amd as A
+    # D and base-2 LSE: two fp32 [B,H,N] arrays, each rounded up to 256 bytes
+    assert A.attn_bwd_workspace_bytes(2, 16, 16, 8192, 128, 128) == 2 * 2 * 16 * 8192 * 4
+    assert A.attn_bwd_workspace_bytes(1, 2, 2, 128, 64, 64) == 2 * 1024
+    assert A.attn_bwd_workspace_bytes(1, 3, 2, 128, 64, 64) == 0      # H % Hkv != 0
+    assert A.attn_bwd_workspace_bytes(1, 2, 2, 100, 64, 64) == 0      # N not a multiple of 128
+    assert A.attn_bwd_workspace_bytes(1, 2, 2, 128, 96, 96) == 0      # unsupported head dim
+
+
+def test_forward_argument_validation(L):
+    import paper_2603_05451_amd as A
+    p = ctypes.c_void_p(0x1000)            # aligned, never dereferenced: validation fails first
+    fwd = lambda *a: L.attn_fwd_ex(*a)
+    assert fwd(None, p, p, p, p, 1, 2, 2, 128, 64, 64, 0.125, 0, None) == A.ATTN_EINVAL
+    assert fwd(p, p, p, p, None, 1, 2, 2, 128, 64, 64, 0.125, 0, None) == A.ATTN_EINVAL
+    assert fwd(p, p, p, p, p, 0, 2, 2, 128, 64, 64, 0.125, 0, None) == A.ATTN_EINVAL
+    assert fwd(p, p, p, p, p, 1, 3, 2, 128, 64, 64, 0.125, 0, None) == A.ATTN_EINVAL
+    assert fwd(p, p, p, p, p, 1, 2, 2, 128, 64, 64, 0.0, 0, None) == A.ATTN_EINVAL
+    assert fwd(p, p, p, p, p, 1, 2, 2, 128, 64, 64, float("nan"), 0, None) == A.ATTN_EINVAL
+    assert fwd(ctypes.c_void_p(0x1008), p, p, p, p, 1, 2, 2, 128, 64, 64, 0.125, 0, None) == A.ATTN_EINVAL
+    assert fwd(p, p, p, p, p, 1, 2, 2, 192, 64, 64, 0.125, 0, None) == A.ATTN_EUNSUPPORTED
+    assert fwd(p, p, p, p, p, 1, 2, 2, 128, 128, 64, 0.125, 0, None) == A.ATTN_EUNSUPPORTED
+    assert L.attn_fwd(p, p, p, p, p, 1, 2, 2, 128, 256, 0.125, 0, None) == A.ATTN_EUNSUPPORTED
+
+
+def test_backward_argument_validation(L):
+    import paper_2603_05451_amd as A
+    p = ctypes.c_void_p(0x1000)
+    ok_ws = A.attn_bwd_workspace_bytes(1, 2, 2, 128, 64, 64)
+    bwd = lambda *a: L.attn_bwd_ex(*a)
+    nine = [p] * 9
+    assert bwd(*nine, 1, 2, 2, 128, 64, 64, 0.125, 0, None, ok_ws, None) == A.ATTN_EINVAL      # no workspace
+    assert bwd(*nine, 1, 2, 2, 128, 64, 64, 0.125, 0, p, ok_ws - 1, None) == A.ATTN_EINVAL     # too small
+    assert bwd(*nine, 1, 2, 2, 128, 64, 64, 0.125, 0, ctypes.c_void_p(0x1010), ok_ws, None) == A.ATTN_EINVAL
+    for i in range(9):
+        args = list(nine)
+        args[i] = None
+        assert bwd(*args, 1, 2, 2, 128, 64, 64, 0.125, 0, p, ok_ws, None) == A.ATTN_EINVAL
+    assert bwd(*nine, 1, 2, 2, 128, 192, 192, 0.125, 0, p, 1 << 20, None) == A.ATTN_EUNSUPPORTED
+    assert L.attn_bwd_phases(*nine, 1, 2, 2, 128, 64, 64, 0.125, 0, p, ok_ws, None, 0) == A.ATTN_EINVAL
+    assert L.attn_bwd_phases(*nine, 1, 2, 2, 128, 64, 64, 0.125, 0, p, ok_ws, None, 8) == A.ATTN_EINVAL
+
+
+def test_input_recipe_is_reproducible():
+    import torch
+    from paper_2603_05451_amd import inputs as I
+    a, b = I.make_inputs(I.CANARY), I.make_inputs(I.CANARY)
+    for n in ("q", "k", "v", "do"):
+        assert a[n].dtype == torch.bfloat16 and torch.equal(a[n], b[n])
+    w = I.Workload("o", 1, 2, 1, 256, 192, 128, True, 5, outlier_frac=0.01)
+    x = I.make_inputs(w)
+    frac_big = (x["q"].float().abs() > 6).float().mean().item()
+    assert 0.002 < frac_big < 0.02          # ~1 % of entries were multiplied by 8
+    assert I.TARGET.fwd_flops() == 4 * 8192 ** 2 * 128 * 16 * 2
+    assert I.GQA.fwd_flops() == 4 * 8192 ** 2 * 128 * 32 * 2 / 2
