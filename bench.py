@@ -18,6 +18,13 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 PEAK_BF16_TFLOPS = 2500.0      # MI355X published dense bf16 MFMA peak
+# HBM bytes per launch on the default workload, from rocprofv3 FETCH_SIZE + WRITE_SIZE (separate
+# --pmc runs, scaled by the same counters' reading for a 1 GiB copy; profiles/bench_target_*.md).
+# They cannot be measured from inside this process; None for any other workload.
+MEASURED_TRAFFIC = {
+    "target_N8192_d128_nc": {"attn_fwd_kernel": 301e6 + 68e6, "attn_bwd_dkdv_kernel": 407e6 + 135e6,
+                             "attn_bwd_dq_kernel": 296e6 + 103e6},
+}
 PAPER_CONTEXT = "paper: up to 1613 TFLOP/s forward (71% of 2.25 PFLOP/s) on B200, BF16 -- other hardware, context only"
 
 
@@ -78,6 +85,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="target")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run one 1 GiB device-to-device copy (reference for rocprofv3 FETCH_SIZE/WRITE_SIZE)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on ONE GPU only (no collectives, no sharding); "
@@ -124,6 +133,11 @@ def main():
     ms_dq = event_ms(lambda: bwd(A.ATTN_BWD_DQ), n)
     bwd()                                    # leave consistent outputs behind
     torch.cuda.synchronize()
+    if args.copy_calibration:
+        src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").normal_()
+        dst = torch.empty_like(src)
+        dst.copy_(src)                       # reads 1 GiB, writes 1 GiB
+        torch.cuda.synchronize()
 
     f_fwd, f_bwd = w.fwd_flops(), w.bwd_flops()
     pairs = w.B * w.H * float(w.N) * w.N * (0.5 if w.causal else 1.0)       # (query, key) pairs
@@ -148,13 +162,16 @@ def main():
         # MFMA units: four contractions (S, dP, dV, dK) of N^2 (d_qk or d_v) multiply-adds each.
         "roofline": {"kernel": "attn_bwd_dkdv_kernel", "bound": "mfma",
                      "achieved": round(tf(f_dkdv, ms_dkdv), 1), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                     "frac": round(tf(f_dkdv, ms_dkdv) / PEAK_BF16_TFLOPS, 4), "traffic": None},
+                     "frac": round(tf(f_dkdv, ms_dkdv) / PEAK_BF16_TFLOPS, 4),
+                     "traffic": MEASURED_TRAFFIC.get(w.name, {}).get("attn_bwd_dkdv_kernel")},
         "roofline_dq": {"kernel": "attn_bwd_dq_kernel", "bound": "mfma",
                         "achieved": round(tf(f_dq, ms_dq), 1), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                        "frac": round(tf(f_dq, ms_dq) / PEAK_BF16_TFLOPS, 4), "traffic": None},
+                        "frac": round(tf(f_dq, ms_dq) / PEAK_BF16_TFLOPS, 4),
+                        "traffic": MEASURED_TRAFFIC.get(w.name, {}).get("attn_bwd_dq_kernel")},
         "roofline_fwd": {"kernel": "attn_fwd_kernel", "bound": "mfma", "achieved": round(tf(f_fwd, ms_fwd), 1),
                          "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                         "frac": round(tf(f_fwd, ms_fwd) / PEAK_BF16_TFLOPS, 4), "traffic": None},
+                         "frac": round(tf(f_fwd, ms_fwd) / PEAK_BF16_TFLOPS, 4),
+                         "traffic": MEASURED_TRAFFIC.get(w.name, {}).get("attn_fwd_kernel")},
         "context": PAPER_CONTEXT,
     }
     if not args.no_cpu_baseline:
