@@ -124,12 +124,16 @@ attn_bwd_dkdv_kernel(const bf16* __restrict__ q, const bf16* __restrict__ k, con
     const int nq = N / BWD_BQ - i_first;
     const int nsteps = G * nq;
 
+    TileCopy<BWD_BQ, DQK, BWD_NT> qcopy;
+    TileCopy<BWD_BQ, DV, BWD_NT> docopy;
+    qcopy.init(q_stride, tid);
+    docopy.init(o_stride, tid);
     auto issue_loads = [&](int step, int buf) {
         const int g = step / nq, i = i_first + (step - g * nq);
         const int hq = kvh * G + g;
         const int64_t row0 = (int64_t)b * N + (int64_t)i * BWD_BQ;
-        tile_load_async<BWD_BQ, DQK, BWD_NT>(q + row0 * q_stride + (int64_t)hq * DQK, q_stride, q_lds[buf], tid);
-        tile_load_async<BWD_BQ, DV, BWD_NT>(d_o + row0 * o_stride + (int64_t)hq * DV, o_stride, do_lds[buf], tid);
+        qcopy.issue_all(q + row0 * q_stride + (int64_t)hq * DQK, q_lds[buf]);
+        docopy.issue_all(d_o + row0 * o_stride + (int64_t)hq * DV, do_lds[buf]);
         if (wave < 2) {   // 64 floats each of lse2 and D
             const float* src = (wave == 0 ? lse2 : D) + ((int64_t)b * H + hq) * N + (int64_t)i * BWD_BQ + lane;
             dma4(src, st_lds + buf * 512 + wave * 256);
@@ -162,8 +166,10 @@ attn_bwd_dkdv_kernel(const bf16* __restrict__ q, const bf16* __restrict__ k, con
 #pragma unroll
         for (int r = 0; r < 16; ++r) dv_acc[db][r] = 0.f;
 
-    for (int step = 0; step < nsteps; ++step) {
-        const int buf = step & 1;
+    // One query tile.  The buffer index is a compile-time constant in the unrolled-by-two loop
+    // below, so every LDS read address is "lane register + immediate".
+    auto q_step = [&](auto bufc, int step) {
+        const int buf = bufc;
         wait_async_copies();
         __syncthreads();           // tiles of this step visible; everyone is done with the previous ones
         if (step + 1 < nsteps) issue_loads(step + 1, buf ^ 1);
@@ -263,6 +269,14 @@ attn_bwd_dkdv_kernel(const bf16* __restrict__ q, const bf16* __restrict__ k, con
                 sched_fence();
             }
         }
+    };
+    if constexpr (DQK <= 128) {
+        for (int step = 0; step < nsteps; step += 2) {   // nsteps is even: N/64 and the causal start are even
+            q_step(std::integral_constant<int, 0>{}, step);
+            q_step(std::integral_constant<int, 1>{}, step + 1);
+        }
+    } else {
+        for (int step = 0; step < nsteps; ++step) q_step(step & 1, step);
     }
 
     // ---- epilogue: dk = scale * dK, dv = dV; accumulators hold the transposes (dims x keys)
@@ -337,8 +351,12 @@ attn_bwd_dq_kernel(const bf16* __restrict__ q, const bf16* __restrict__ k, const
     const bf16* vg = v + ((int64_t)b * N * Hkv + kvh) * DV;
     const int ntiles = CAUSAL ? (q0 + DQ_BM) / DQ_BN : N / DQ_BN;
 
-    tile_load_async<DQ_BN, DQK, BWD_NT>(kg, k_stride, k_lds[0], tid);
-    tile_load_async<DQ_BN, DV, BWD_NT>(vg, v_stride, v_lds[0], tid);
+    TileCopy<DQ_BN, DQK, BWD_NT> kcopy;
+    TileCopy<DQ_BN, DV, BWD_NT> vcopy;
+    kcopy.init(k_stride, tid);
+    vcopy.init(v_stride, tid);
+    kcopy.issue_all(kg, k_lds[0]);
+    vcopy.issue_all(vg, v_lds[0]);
 
     // this wave's Q and dO rows as B operands: lane = query qw0 + c, dims 16*ks + 8h .. +7
     bf16x8 qf[KSQ], dof[KSV];
@@ -366,52 +384,18 @@ attn_bwd_dq_kernel(const bf16* __restrict__ q, const bf16* __restrict__ k, const
 #pragma unroll
         for (int r = 0; r < 16; ++r) dq_acc[db][r] = 0.f;
 
-    for (int j = 0; j < ntiles; ++j) {
-        const int buf = j & 1;
+    auto tile_step = [&](auto bufc, int j) {
+        const int buf = bufc;               // compile-time constant in the unrolled variants
         wait_async_copies();
         __syncthreads();
         if (j + 1 < ntiles) {
-            tile_load_async<DQ_BN, DQK, BWD_NT>(kg + (int64_t)(j + 1) * DQ_BN * k_stride, k_stride, k_lds[buf ^ 1], tid);
-            tile_load_async<DQ_BN, DV, BWD_NT>(vg + (int64_t)(j + 1) * DQ_BN * v_stride, v_stride, v_lds[buf ^ 1], tid);
+            kcopy.issue_all(kg + (int64_t)(j + 1) * DQ_BN * k_stride, k_lds[buf ^ 1]);
+            vcopy.issue_all(vg + (int64_t)(j + 1) * DQ_BN * v_stride, v_lds[buf ^ 1]);
         }
         const int key0 = j * DQ_BN;
-        if (CAUSAL && key0 > qw0 + 31) continue;
+        if (CAUSAL && key0 > qw0 + 31) return;
 
-        // ---- S^T = K Q_w^T and dP^T = V dO_w^T, KB blocks of 32 keys x 32 queries each
-        f32x16 s[KB], dp[KB];
-#pragma unroll
-        for (int kb = 0; kb < KB; ++kb)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) { s[kb][r] = 0.f; dp[kb][r] = 0.f; }
-        {
-            constexpr int GRP = 4, PER = KSQ + KSV, NG = KB * PER / GRP;
-            static_assert(KSQ % GRP == 0 && KSV % GRP == 0, "k-steps must split into whole groups");
-            bf16x8 fr[2][GRP];
-            auto load_a = [&](int g, bf16x8* dst) {
-#pragma unroll
-                for (int t = 0; t < GRP; ++t) {
-                    const int st = g * GRP + t, kb = st / PER, u = st % PER;
-                    dst[t] = u < KSQ
-                        ? lds_read_b128(k_lds[buf] + tile_off<DQK>(32 * kb + c, 2 * u + h))
-                        : lds_read_b128(v_lds[buf] + tile_off<DV>(32 * kb + c, 2 * (u - KSQ) + h));
-                }
-            };
-            load_a(0, fr[0]);
-#pragma unroll
-            for (int g = 0; g < NG; ++g) {
-                if (g + 1 < NG) load_a(g + 1, fr[(g + 1) & 1]);
-                sched_fence();
-#pragma unroll
-                for (int t = 0; t < GRP; ++t) {
-                    const int st = g * GRP + t, kb = st / PER, u = st % PER;
-                    if (u < KSQ) s[kb] = mfma32(fr[g & 1][t], qf[u], s[kb]);
-                    else dp[kb] = mfma32(fr[g & 1][t], dof[u - KSQ], dp[kb]);
-                }
-                sched_fence();
-            }
-        }
-
-        // first group of K^T fragments: in flight during the elementwise work
+        // K^T fragments for the dQ contraction (transposing reads of the same K tile)
         bf16x4 tfr[2][DBQ][2];
         auto load_t = [&](int kk, bf16x4 (*dst)[2]) {
             const ATTN_LDS char* base = k_lds[buf] + tr_half;
@@ -421,20 +405,65 @@ attn_bwd_dq_kernel(const bf16* __restrict__ q, const bf16* __restrict__ k, const
                 dst[db][1] = lds_read_tr(base + tile_off<DQK>(16 * kk + 8 + tr_row, 4 * db + tr_chunk));
             }
         };
-        load_t(0, tfr[0]);
-        sched_fence();
 
-        // ---- dS^T = P^T o (dP^T - D), P^T = 2^(c S^T - LSE2); the key index is the register row
+        // ---- per block of 32 keys: S^T = K Q_w^T, dP^T = V dO_w^T, then
+        // dS^T = P^T o (dP^T - D) with P^T = 2^(c S^T - LSE2); the key index is the register row.
+        // One accumulator pair is reused for both key blocks (register budget: 2 waves per SIMD).
         const bool diag = CAUSAL && (key0 + DQ_BN - 1 > qw0);
         bf16x8 dsf[KB][2];
 #pragma unroll
-        for (int kb = 0; kb < KB; ++kb)
+        for (int kb = 0; kb < KB; ++kb) {
+            f32x16 s, dp;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) { s[r] = 0.f; dp[r] = 0.f; }
+#ifndef ATTN_DQ_GRP
+#define ATTN_DQ_GRP 2
+#endif
+            constexpr int GRP = ATTN_DQ_GRP, PER = KSQ + KSV, NG = PER / GRP;
+            static_assert(KSQ % GRP == 0 && KSV % GRP == 0, "k-steps must split into whole groups");
+            bf16x8 fr[2][GRP];
+            auto load_a = [&](int g, bf16x8* dst) {
+#pragma unroll
+                for (int t = 0; t < GRP; ++t) {
+                    // alternate K and V fragments so that the S and dP accumulation chains
+                    // interleave; the K-only remainder (d_qk > d_v) comes last
+                    const int st = g * GRP + t;
+                    const bool from_k = st >= 2 * KSV || (st & 1) == 0;
+                    const int u = st >= 2 * KSV ? st - KSV : st >> 1;
+                    dst[t] = from_k
+                        ? lds_read_b128(k_lds[buf] + tile_off<DQK>(32 * kb + c, 2 * u + h))
+                        : lds_read_b128(v_lds[buf] + tile_off<DV>(32 * kb + c, 2 * u + h));
+                }
+            };
+            static_assert(KSQ >= KSV, "interleave assumes d_qk >= d_v");
+            load_a(0, fr[0]);
+#pragma unroll
+            for (int g = 0; g < NG; ++g) {
+                if (g + 1 < NG) load_a(g + 1, fr[(g + 1) & 1]);
+                sched_fence();
+#pragma unroll
+                for (int t = 0; t < GRP; ++t) {
+                    const int st = g * GRP + t;
+                    const bool from_k = st >= 2 * KSV || (st & 1) == 0;
+                    const int u = st >= 2 * KSV ? st - KSV : st >> 1;
+                    if (from_k) s = mfma32(fr[g & 1][t], qf[u], s);
+                    else dp = mfma32(fr[g & 1][t], dof[u], dp);
+                }
+                sched_fence();
+            }
+            if (kb == KB - 1) { load_t(0, tfr[0]); sched_fence(); }   // in flight during the last elementwise block
+            if (diag) {   // masked scores -> -inf -> P = 0 -> dS = 0
+                const int lim = qw0 + c - key0 - 32 * kb - 4 * h;      // register row 8(r/4) + r%4 > lim is masked
+#pragma unroll
+                for (int r = 0; r < 16; ++r)
+                    if (8 * (r >> 2) + (r & 3) > lim) s[r] = -INFINITY;
+            }
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
-                float p = fast_exp2(fmaf(s[kb][r], scale_log2e, -lse_q));
-                if (diag && (key0 + 32 * kb + acc_row(r, h) > qw0 + c)) p = 0.f;
-                dsf[kb][r >> 3][r & 7] = (bf16)(p * (dp[kb][r] - D_q));
+                const float p = fast_exp2(fmaf(s[r], scale_log2e, -lse_q));
+                dsf[kb][r >> 3][r & 7] = (bf16)(p * (dp[r] - D_q));
             }
+        }
 
         // ---- dQ_w^T += K^T dS^T : contraction over the 64 keys in 4 steps of 16
 #pragma unroll
@@ -446,6 +475,14 @@ attn_bwd_dq_kernel(const bf16* __restrict__ q, const bf16* __restrict__ k, const
                 dq_acc[db] = mfma32(cat4(tfr[kk & 1][db][0], tfr[kk & 1][db][1]), dsf[kk >> 1][kk & 1], dq_acc[db]);
             sched_fence();
         }
+    };
+    if constexpr (DQK <= 128) {
+        for (int j = 0; j < ntiles; j += 2) {      // ntiles is even
+            tile_step(std::integral_constant<int, 0>{}, j);
+            tile_step(std::integral_constant<int, 1>{}, j + 1);
+        }
+    } else {
+        for (int j = 0; j < ntiles; ++j) tile_step(j & 1, j);
     }
 
     // ---- epilogue: dq = scale * dQ; the accumulator holds the transpose (dims x queries)

@@ -28,8 +28,11 @@ constexpr int FWD_BM = 128;   // query rows per block
 constexpr int FWD_BN = 64;    // keys per tile
 constexpr int FWD_NT = 256;
 
+#ifndef ATTN_FWD_OCC192
+#define ATTN_FWD_OCC192 2
+#endif
 template <int DQK, int DV, bool CAUSAL>
-__global__ void __launch_bounds__(FWD_NT, 2)
+__global__ void __launch_bounds__(FWD_NT, (DQK > 128 ? ATTN_FWD_OCC192 : 2))
 attn_fwd_kernel(const bf16* __restrict__ q, const bf16* __restrict__ k, const bf16* __restrict__ v,
                 bf16* __restrict__ o, float* __restrict__ lse,
                 int H, int Hkv, int N, float scale_log2e)
@@ -72,8 +75,12 @@ attn_fwd_kernel(const bf16* __restrict__ q, const bf16* __restrict__ k, const bf
     const int ntiles = CAUSAL ? (q0 + FWD_BM) / FWD_BN : N / FWD_BN;
 
     // prologue: start the copy of tile 0
-    tile_load_async<FWD_BN, DQK, FWD_NT>(kg, k_stride, k_lds[0], tid);
-    tile_load_async<FWD_BN, DV, FWD_NT>(vg, v_stride, v_lds[0], tid);
+    TileCopy<FWD_BN, DQK, FWD_NT> kcopy;
+    TileCopy<FWD_BN, DV, FWD_NT> vcopy;
+    kcopy.init(k_stride, tid);
+    vcopy.init(v_stride, tid);
+    kcopy.issue_all(kg, k_lds[0]);
+    vcopy.issue_all(vg, v_lds[0]);
 
     // Q fragments (B operand of S^T = K Q^T): lane holds query qw0 + c, dims 16*ks + 8h .. +7
     bf16x8 qf[KS];
@@ -101,18 +108,19 @@ attn_fwd_kernel(const bf16* __restrict__ q, const bf16* __restrict__ k, const bf
     const int v_chunk0 = 2 * ((lane >> 4) & 1) + ((i16 & 3) >> 1);
     const int v_half = (i16 & 1) * 8;
 
-    for (int j = 0; j < ntiles; ++j) {
-        const int buf = j & 1;
+    // One KV tile.  The buffer index is a template constant (the loop below is unrolled by two)
+    // so that every LDS read address is "lane register + immediate": no per-tile address
+    // arithmetic on the vector ALU.
+    auto tile_step = [&](auto bufc, int j) {
+        const int buf = bufc;               // compile-time constant in the unrolled variants
         wait_async_copies();
         __syncthreads();                    // tile j visible to all; everyone is done with tile j-1
         if (j + 1 < ntiles) {
-            tile_load_async<FWD_BN, DQK, FWD_NT>(kg + (int64_t)(j + 1) * FWD_BN * k_stride, k_stride,
-                                                 k_lds[buf ^ 1], tid);
-            tile_load_async<FWD_BN, DV, FWD_NT>(vg + (int64_t)(j + 1) * FWD_BN * v_stride, v_stride,
-                                                v_lds[buf ^ 1], tid);
+            kcopy.issue_all(kg + (int64_t)(j + 1) * FWD_BN * k_stride, k_lds[buf ^ 1]);
+            vcopy.issue_all(vg + (int64_t)(j + 1) * FWD_BN * v_stride, v_lds[buf ^ 1]);
         }
         const int key0 = j * FWD_BN;
-        if (CAUSAL && key0 > qw0 + 31) continue;   // whole tile above this wave's diagonal
+        if (CAUSAL && key0 > qw0 + 31) return;     // whole tile above this wave's diagonal
 
         // ---- S^T = K Q^T : KB blocks of 32 keys x 32 queries.  LDS reads run one group of
         // GRP fragments ahead of the MFMAs that consume them.
@@ -208,6 +216,14 @@ attn_fwd_kernel(const bf16* __restrict__ q, const bf16* __restrict__ k, const bf
                 oacc[db] = mfma32(cat4(vfr[kk & 1][db][0], vfr[kk & 1][db][1]), pf[kk >> 1][kk & 1], oacc[db]);
             sched_fence();
         }
+    };
+    if constexpr (DQK <= 128) {
+        for (int j = 0; j < ntiles; j += 2) {      // ntiles is even (N and the causal bound are multiples of 128)
+            tile_step(std::integral_constant<int, 0>{}, j);
+            tile_step(std::integral_constant<int, 1>{}, j + 1);
+        }
+    } else {                                       // d_qk = 192: the unrolled body does not fit 256 VGPRs
+        for (int j = 0; j < ntiles; ++j) tile_step(j & 1, j);
     }
 
     // ---- epilogue: O = acc / l, LSE = ln2 * (m_ref + log2 l)   (relative to the reference used)

@@ -4,6 +4,7 @@
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#include <type_traits>
 
 namespace attn {
 
@@ -128,6 +129,56 @@ __device__ __forceinline__ void tile_load_async(const bf16* __restrict__ g, int6
         const int row = p / CPR;
         const int chunk = swz_chunk<D>(row, p % CPR);   // XOR is its own inverse
         dma16(g + (int64_t)row * gstride + chunk * 8, lds + p0 * 16);
+    }
+}
+
+// Tile copy for the main loops.  The per-lane byte offsets inside a tile and the wave's LDS
+// slice offsets are computed once (init); a tile is then copied with N wave instructions that
+// take the tile's global base address in SGPRs (advanced with scalar arithmetic per tile) and
+// the lane offset in one VGPR: no vector ALU work per tile.
+template <int ROWS, int D, int NT>
+struct TileCopy {
+    static constexpr int N = ROWS * (D / 8) / NT;   // wave instructions per thread and tile
+    uint32_t goff[N];                                // byte offset of this lane's 16 bytes inside the tile
+    uint32_t loff[N];                                // byte offset of the wave's 1 KiB slice in the LDS tile
+    __device__ __forceinline__ void init(int64_t gstride, int tid)
+    {
+        constexpr int CPR = D / 8;
+        const int wave = tid >> 6, lane = tid & 63;
+#pragma unroll
+        for (int t = 0; t < N; ++t) {
+            const int p0 = (t * (NT / 64) + wave) * 64;
+            const int p = p0 + lane;
+            const int row = p / CPR;
+            goff[t] = (uint32_t)(row * (int)gstride + swz_chunk<D>(row, p % CPR) * 8) * 2u;
+            loff[t] = __builtin_amdgcn_readfirstlane((uint32_t)(p0 * 16));
+        }
+    }
+    // gtile must be wave-uniform (it is passed in SGPRs)
+    __device__ __forceinline__ void issue(int t, const bf16* gtile, ATTN_LDS char* lds_tile) const
+    {
+        const uint32_t m0 = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)lds_tile) + loff[t];
+        const uint64_t base = (uint64_t)gtile;
+        const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)base);
+        const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)(base >> 32));
+        const uint64_t sbase = ((uint64_t)hi << 32) | lo;
+        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                     :: "s"(m0), "v"(goff[t]), "s"(sbase) : "memory");
+    }
+    __device__ __forceinline__ void issue_all(const bf16* gtile, ATTN_LDS char* lds_tile) const
+    {
+#pragma unroll
+        for (int t = 0; t < N; ++t) issue(t, gtile, lds_tile);
+    }
+};
+
+// Compile-time loop: f(std::integral_constant<int, I>) for I = 0 .. N-1.
+template <int I, int N, typename F>
+__device__ __forceinline__ void static_for(F&& f)
+{
+    if constexpr (I < N) {
+        f(std::integral_constant<int, I>{});
+        static_for<I + 1, N>(f);
     }
 }
 
