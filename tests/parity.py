@@ -46,6 +46,21 @@ def assert_close(got, ref, what, max_abs=MAX_ABS, rel_fro=REL_FRO):
     return ma, rf
 
 
+def assert_close_wide(got, ref, what):
+    """For outputs whose magnitude exceeds 8 on N(0,1) inputs (dK/dV summed over 8 query heads of
+    one KV head): one bf16 half-ulp of the OUTPUT is then already above 2e-2, so the absolute
+    bound gets the output-rounding term, |got - ref| <= 2e-2 + 2^-8 |ref|; relative Frobenius
+    1e-2 unchanged."""
+    got = np.asarray(got, dtype=np.float64)
+    ref = np.asarray(ref, dtype=np.float64)
+    ma, rf = errors(got, ref)
+    REPORT.append((what + " [+output ulp]", ma, rf))
+    excess = np.abs(got - ref) - (MAX_ABS + 2.0 ** -8 * np.abs(ref))
+    assert excess.max() <= 0 and rf <= REL_FRO, \
+        f"{what}: worst excess {excess.max():.3e}, max-abs {ma:.3e}, rel-Fro {rf:.3e}"
+    return ma, rf
+
+
 def assert_close_terms(got, ref, mag, what):
     """Gate for the heavy-tailed workload: see the module docstring.  mag = A, same shape."""
     got = np.asarray(got, dtype=np.float64)
