@@ -78,6 +78,34 @@ def cpu_baseline(w, x, seconds_target=8.0):
                       f"query rows against all {w.N} keys, {dt:.1f} s"}
 
 
+def write_table(path, workloads, n=10, warm=5):
+    """Forward and backward time of every workload (paper Sec. 5 protocol: 5 warm-up runs, 10 timed
+    runs, mean; HIP events) as a markdown table."""
+    import torch
+    import paper_2603_05451_amd as A
+    from paper_2603_05451_amd import inputs as I
+    rows = ["| workload | B | H/Hkv | N | d_qk/d_v | causal | fwd ms | fwd TFLOP/s | % peak | bwd ms | bwd TFLOP/s | % peak |",
+            "|---|---|---|---|---|---|---|---|---|---|---|---|"]
+    for w in workloads:
+        x = I.make_inputs(w)
+        q, k, v, do = (x[n].cuda() for n in ("q", "k", "v", "do"))
+        o = torch.empty((w.B, w.N, w.H, w.dv), dtype=torch.bfloat16, device="cuda")
+        lse = torch.empty((w.B, w.H, w.N), dtype=torch.float32, device="cuda")
+        dq, dk, dv = torch.empty_like(q), torch.empty_like(k), torch.empty_like(v)
+        ws = torch.empty(A.attn_bwd_workspace_bytes(w.B, w.H, w.Hkv, w.N, w.dqk, w.dv), dtype=torch.uint8, device="cuda")
+        fwd = lambda: A.attn_fwd(q, k, v, w.scale, w.causal, o, lse)
+        bwd = lambda: A.attn_bwd(q, k, v, o, do, lse, w.scale, w.causal, dq, dk, dv, ws)
+        for _ in range(warm):
+            fwd(); bwd()
+        mf, mb = event_ms(fwd, n), event_ms(bwd, n)
+        tf, tb = w.fwd_flops() / mf / 1e9, w.bwd_flops() / mb / 1e9
+        rows.append(f"| {w.name} | {w.B} | {w.H}/{w.Hkv} | {w.N} | {w.dqk}/{w.dv} | {int(w.causal)} | {mf:.3f} | {tf:.0f} | "
+                    f"{100 * tf / PEAK_BF16_TFLOPS:.1f} | {mb:.3f} | {tb:.0f} | {100 * tb / PEAK_BF16_TFLOPS:.1f} |")
+        del q, k, v, do, o, lse, dq, dk, dv, ws
+    with open(path, "w") as f:
+        f.write("\n".join(rows) + "\n")
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -85,6 +113,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="target")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--table", metavar="FILE", default=None,
+                    help="also time every workload of the task's config list and write a markdown table to FILE")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one 1 GiB device-to-device copy (reference for rocprofv3 FETCH_SIZE/WRITE_SIZE)")
     args = ap.parse_args()
@@ -176,6 +206,9 @@ def main():
     }
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w, x)
+    if args.table:
+        del q, k, v, do, o, lse, dq, dk, dv, ws
+        write_table(args.table, [I.CANARY] + I.SWEEP_D64_NC + I.SWEEP_D128_C + [I.TARGET, I.GQA, I.MLA_OUTLIER])
     print(json.dumps(out))
 
 
