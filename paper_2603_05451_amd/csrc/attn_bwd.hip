@@ -76,7 +76,7 @@ bwd_prepare_kernel(const bf16* __restrict__ o, const bf16* __restrict__ d_o, con
 // bwd_dkdv: block = 4 waves = 128 keys (32 per wave); query tiles of 64 rows stream through
 // LDS (double buffered, direct global->LDS copies).
 template <int DQK, int DV, bool CAUSAL>
-__global__ void __launch_bounds__(BWD_NT, 1)
+__global__ void __launch_bounds__(BWD_NT, (DQK <= 64 ? 2 : 1))
 attn_bwd_dkdv_kernel(const bf16* __restrict__ q, const bf16* __restrict__ k, const bf16* __restrict__ v,
                      const bf16* __restrict__ d_o, const float* __restrict__ lse2, const float* __restrict__ D,
                      bf16* __restrict__ dk, bf16* __restrict__ dv,
