@@ -99,6 +99,19 @@ int attn_bwd_phases(const void* q, const void* k, const void* v, const void* o, 
  * D and the base-2 LSE, [B,H,N] fp32 each (256-byte aligned sections). */
 size_t attn_bwd_workspace_bytes(int B, int H, int Hkv, int N, int d_qk, int d_v);
 
+/* Software 2^x of paper Sec. 3.1.3 (range reduction + degree-n minimax polynomial, p0 = 1, Horner
+ * with FMAs, exponent splice), provided to measure it on this hardware; attn_fwd does not use
+ * it (v_exp_f32 and the FMAs share one issue port on CDNA4, so emulation cannot add throughput).
+ *   attn_exp2_emulated: y[i] = 2^x[i] for n fp32 values; degree 3, 4 or 5, or 0 for the hardware
+ *       instruction.  x, y: device pointers, 4-byte aligned, may not overlap partially.
+ *   attn_exp2_rate: enqueues a pure-ALU kernel of ATTN_EXP2_RATE_BLOCKS x 256 threads, each
+ *       doing 8 x iters evaluations, writing one float per thread to out (device,
+ *       ATTN_EXP2_RATE_BLOCKS * 256 floats); returns the number of evaluations enqueued (> 0),
+ *       or a negative error code.  The caller times it on the stream. */
+enum { ATTN_EXP2_RATE_BLOCKS = 2048 };
+int attn_exp2_emulated(const float* x, float* y, size_t n, int degree, void* stream);
+long long attn_exp2_rate(float* out, int degree, int iters, void* stream);
+
 /* Human-readable text for a return code (static storage). */
 const char* attn_strerror(int code);
 

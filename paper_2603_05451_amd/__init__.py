@@ -47,6 +47,10 @@ def lib():
         L.attn_bwd_phases.restype = i
         L.attn_bwd_workspace_bytes.argtypes = [i] * 6
         L.attn_bwd_workspace_bytes.restype = sz
+        L.attn_exp2_emulated.argtypes = [vp, vp, sz, i, vp]
+        L.attn_exp2_emulated.restype = i
+        L.attn_exp2_rate.argtypes = [vp, i, i, vp]
+        L.attn_exp2_rate.restype = ctypes.c_longlong
         L.attn_strerror.argtypes = [i]
         L.attn_strerror.restype = ctypes.c_char_p
         L.attn_version.restype = i
@@ -105,6 +109,31 @@ def attn_fwd(q, k, v, scale, causal, o=None, lse=None, stream=None):
                            float(scale), int(bool(causal)), _stream(stream))
     _check(rc)
     return o, lse
+
+
+ATTN_EXP2_RATE_BLOCKS = 2048
+
+
+def attn_exp2_emulated(x, degree, y=None, stream=None):
+    """y = 2^x elementwise on the GPU: polynomial emulation of degree 3/4/5, or 0 = v_exp_f32."""
+    import torch
+    if not (x.is_cuda and x.dtype == torch.float32 and x.is_contiguous()):
+        raise ValueError("x must be a contiguous fp32 CUDA tensor")
+    y = torch.empty_like(x) if y is None else y
+    _check(lib().attn_exp2_emulated(ctypes.c_void_p(x.data_ptr()), ctypes.c_void_p(y.data_ptr()),
+                                    x.numel(), int(degree), _stream(stream)))
+    return y
+
+
+def attn_exp2_rate(degree, iters, out=None, stream=None):
+    """Enqueue the pure-ALU exp2 throughput kernel; returns (number of evaluations, out tensor)."""
+    import torch
+    if out is None:
+        out = torch.empty(ATTN_EXP2_RATE_BLOCKS * 256, dtype=torch.float32, device="cuda")
+    n = lib().attn_exp2_rate(ctypes.c_void_p(out.data_ptr()), int(degree), int(iters), _stream(stream))
+    if n <= 0:
+        _check(int(n) or ATTN_EINVAL)
+    return int(n), out
 
 
 ATTN_BWD_PREPARE, ATTN_BWD_DKDV, ATTN_BWD_DQ, ATTN_BWD_ALL = 1, 2, 4, 7

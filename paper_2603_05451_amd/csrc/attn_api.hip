@@ -20,8 +20,10 @@ int check_sizes(int B, int H, int Hkv, int N, int d_qk, int d_v)
     if (H % Hkv != 0) return ATTN_EINVAL;
     if (!dims_supported(d_qk, d_v)) return ATTN_EUNSUPPORTED;
     if (N % 128 != 0) return ATTN_EUNSUPPORTED;
-    // element offsets are 64-bit, but row indices B*N*H must fit a 32-bit grid
+    // element offsets are 64-bit, but the grid index B*H*(N/128) and the byte offsets inside
+    // one 128-row tile (row stride H * d * 2 bytes) are 32-bit
     if ((int64_t)B * H * (N / 128) > 0x7fffffffLL) return ATTN_EUNSUPPORTED;
+    if ((int64_t)H * (d_qk > d_v ? d_qk : d_v) * 2 * 128 > 0x7fffffffLL) return ATTN_EUNSUPPORTED;
     return ATTN_OK;
 }
 

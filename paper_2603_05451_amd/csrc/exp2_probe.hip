@@ -1,0 +1,104 @@
+// Software 2^x on the vector ALU (paper Sec. 3.1.3), built to MEASURE it on gfx950, not to use
+// it: on this hardware v_exp_f32 issues from the same VALU port as the FMAs that would emulate
+// it, so the emulation cannot add exponential throughput (see the throughput entry point).
+//
+// Steps of the section: clamp to >= -127; floor (v_floor_f32 here; the section's
+// add-and-subtract of 2^23 + 2^22 in round-down mode computes the same function); fractional
+// part; polynomial with p0 = 1 by Horner's rule with FMAs; integer part shifted into the exponent
+// field and added to the polynomial's bits.  Coefficients: minimax relative error on [0, 1),
+// from gen_exp2_coeffs.py (Remez exchange); the section prints none.
+#include "../../include/attn.h"
+#include "launch.h"
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace attn {
+
+template <int DEG> struct Exp2Poly;
+template <> struct Exp2Poly<3> { static constexpr float p[3] = {6.951167583e-01f, 2.276449949e-01f, 7.706703991e-02f}; };
+template <> struct Exp2Poly<4> { static constexpr float p[4] = {6.930448413e-01f, 2.412801981e-01f, 5.224247277e-02f, 1.342668384e-02f}; };
+template <> struct Exp2Poly<5> { static constexpr float p[5] = {6.931512952e-01f, 2.401644439e-01f, 5.579991266e-02f, 9.017030708e-03f, 1.867130050e-03f}; };
+
+template <int DEG>
+__device__ __forceinline__ float exp2_emulated(float x)
+{
+    x = fmaxf(x, -127.0f);
+    const float fl = __builtin_floorf(x);
+    const float f = x - fl;
+    float acc = Exp2Poly<DEG>::p[DEG - 1];
+#pragma unroll
+    for (int i = DEG - 2; i >= 0; --i) acc = __builtin_fmaf(acc, f, Exp2Poly<DEG>::p[i]);
+    acc = __builtin_fmaf(acc, f, 1.0f);
+    return __int_as_float(__float_as_int(acc) + ((int)fl << 23));
+}
+
+template <int DEG>
+__global__ void __launch_bounds__(256) exp2_map_kernel(const float* __restrict__ x, float* __restrict__ y, size_t n)
+{
+    const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (i >= n) return;
+    if constexpr (DEG == 0) y[i] = __builtin_amdgcn_exp2f(x[i]);
+    else y[i] = exp2_emulated<DEG>(x[i]);
+}
+
+// ALU throughput: 8 independent evaluations per thread and iteration, arguments kept in [0, 1)
+template <int DEG>
+__global__ void __launch_bounds__(256) exp2_rate_kernel(float* __restrict__ out, int iters)
+{
+    float v[8], s[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) { v[e] = 0.03f * e + 1e-4f * threadIdx.x; s[e] = 0.f; }
+    for (int it = 0; it < iters; ++it)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            float r;
+            if constexpr (DEG == 0) r = __builtin_amdgcn_exp2f(v[e]);
+            else r = exp2_emulated<DEG>(v[e]);
+            s[e] += r;
+            v[e] = r - 1.0f;              // back into [0, 1): a dependent chain per slot, 8 slots in flight
+        }
+    float t = 0.f;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) t += s[e];
+    out[(size_t)blockIdx.x * 256 + threadIdx.x] = t;
+}
+
+}  // namespace attn
+
+extern "C" {
+
+int attn_exp2_emulated(const float* x, float* y, size_t n, int degree, void* stream)
+{
+    using namespace attn;
+    if (!x || !y || n == 0) return ATTN_EINVAL;
+    const dim3 grid((unsigned)((n + 255) / 256)), block(256);
+    hipError_t e;
+    switch (degree) {
+        case 0: e = launch_kernel(exp2_map_kernel<0>, grid, block, 0, stream, x, y, n); break;
+        case 3: e = launch_kernel(exp2_map_kernel<3>, grid, block, 0, stream, x, y, n); break;
+        case 4: e = launch_kernel(exp2_map_kernel<4>, grid, block, 0, stream, x, y, n); break;
+        case 5: e = launch_kernel(exp2_map_kernel<5>, grid, block, 0, stream, x, y, n); break;
+        default: return ATTN_EUNSUPPORTED;
+    }
+    return e == hipSuccess ? ATTN_OK : ATTN_ELAUNCH;
+}
+
+long long attn_exp2_rate(float* out, int degree, int iters, void* stream)
+{
+    using namespace attn;
+    if (!out || iters <= 0) return ATTN_EINVAL;
+    const dim3 grid(ATTN_EXP2_RATE_BLOCKS), block(256);
+    hipError_t e;
+    switch (degree) {
+        case 0: e = launch_kernel(exp2_rate_kernel<0>, grid, block, 0, stream, out, iters); break;
+        case 3: e = launch_kernel(exp2_rate_kernel<3>, grid, block, 0, stream, out, iters); break;
+        case 4: e = launch_kernel(exp2_rate_kernel<4>, grid, block, 0, stream, out, iters); break;
+        case 5: e = launch_kernel(exp2_rate_kernel<5>, grid, block, 0, stream, out, iters); break;
+        default: return ATTN_EUNSUPPORTED;
+    }
+    if (e != hipSuccess) return ATTN_ELAUNCH;
+    return (long long)ATTN_EXP2_RATE_BLOCKS * 256 * 8 * iters;
+}
+
+}  // extern "C"

@@ -1,0 +1,73 @@
+"""GPU software-exp2 (paper Sec. 3.1.3) against the numpy oracle and the paper's accuracy table."""
+import os
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import exp2_emulation as E
+
+pytestmark = pytest.mark.gpu
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden", "exp2_accuracy_table.txt")
+
+
+def table():
+    return {ln.split()[0]: [float(v) for v in ln.split()[1:]] for ln in open(GOLDEN)
+            if ln.strip() and not ln.startswith("#")}
+
+
+@pytest.mark.parametrize("degree", [3, 4, 5])
+def test_gpu_emulation_matches_oracle_and_table(degree):
+    import paper_2603_05451_amd as A
+    rng = np.random.default_rng(7)
+    x = np.concatenate([rng.random(1 << 22, dtype=np.float32),                       # the table's domain
+                        rng.uniform(-126, 40, 1 << 16).astype(np.float32),           # range reduction
+                        np.array([-1e4, -127.0, -126.5, -1.0, 0.0, 1.0, 17.0], np.float32)])
+    y = A.attn_exp2_emulated(torch.from_numpy(x).cuda(), degree).cpu().numpy()
+    ref = E.exp2_emulated(x, E.fit_coefficients(degree))
+    # the oracle's coefficients come from a linear program, the kernel's from a Remez exchange:
+    # the two fits agree to the last fp32 digit or two, so results agree within a few ulp
+    rel = np.abs(y.astype(np.float64) - ref.astype(np.float64)) / np.maximum(np.abs(ref), 1e-37)
+    assert rel.max() <= (1e-6 if degree < 5 else 2e-7 * 5), rel.max()
+    assert y[-7] == 0.0 and y[-6] == 0.0 and y[-3] == 1.0 and y[-2] == 2.0 and y[-1] == 131072.0
+    # and the GPU result reproduces the paper's error levels on [0, 1)
+    want = table()[f"degree{degree}"]
+    x01 = x[:1 << 22]
+    true = np.exp2(x01.astype(np.float64))
+    e32 = np.abs(y[:1 << 22].astype(np.float64) - true) / true
+    e16 = np.abs(E.to_bf16(y[:1 << 22]).astype(np.float64) - true) / true
+    assert abs(e32.mean() - want[1]) <= 0.05 * want[1]
+    assert abs(e32.max() - want[0]) <= (0.5 if degree == 5 else 0.10) * want[0]
+    assert abs(e16.max() - want[2]) <= 0.02 * want[2] and abs(e16.mean() - want[3]) <= 0.02 * want[3]
+
+
+def test_hardware_exp2_matches_table_row():
+    import paper_2603_05451_amd as A
+    x = np.random.default_rng(8).random(1 << 22, dtype=np.float32)
+    y = A.attn_exp2_emulated(torch.from_numpy(x).cuda(), 0).cpu().numpy()
+    true = np.exp2(x.astype(np.float64))
+    e32 = np.abs(y.astype(np.float64) - true) / true
+    # v_exp_f32 is a different unit from the paper's MUFU.EX2: same order of magnitude (1 ulp class)
+    assert e32.max() < 3e-7 and e32.mean() < 6e-8
+
+
+def test_emulation_is_slower_than_the_hardware_instruction(capsys):
+    """The measurement behind keeping emulation off the path: evaluations per second of each
+    variant, pure ALU, whole chip."""
+    import paper_2603_05451_amd as A
+    rates = {}
+    for degree in (0, 3, 4, 5):
+        A.attn_exp2_rate(degree, 64)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        n, out = A.attn_exp2_rate(degree, 2000)
+        e1.record()
+        e1.synchronize()
+        assert torch.isfinite(out).all()
+        rates[degree] = n / (e0.elapsed_time(e1) * 1e-3) / 1e12
+    print("exp2 evaluations per second (T/s):", {k: round(v, 2) for k, v in rates.items()})
+    path = os.path.join(os.path.dirname(os.path.dirname(__file__)), "gpurun_out", "exp2_rates.txt")
+    os.makedirs(os.path.dirname(path), exist_ok=True)
+    with open(path, "w") as f:
+        f.write("degree (0 = v_exp_f32) : T evaluations / s\n" + "\n".join(f"{k} : {v:.3f}" for k, v in rates.items()) + "\n")
+    assert rates[3] < rates[0] and rates[4] < rates[0] and rates[5] < rates[0]
