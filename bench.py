@@ -22,8 +22,8 @@ PEAK_BF16_TFLOPS = 2500.0      # MI355X published dense bf16 MFMA peak
 # --pmc runs, scaled by the same counters' reading for a 1 GiB copy; profiles/bench_target_*.md).
 # They cannot be measured from inside this process; None for any other workload.
 MEASURED_TRAFFIC = {
-    "target_N8192_d128_nc": {"attn_fwd_kernel": 301e6 + 68e6, "attn_bwd_dkdv_kernel": 407e6 + 135e6,
-                             "attn_bwd_dq_kernel": 296e6 + 103e6},
+    "target_N8192_d128_nc": {"attn_fwd_kernel": 287e6 + 68e6, "attn_bwd_dkdv_ws_kernel": 407e6 + 134e6,
+                             "attn_bwd_dq_kernel": 375e6 + 67e6},
 }
 PAPER_CONTEXT = "paper: up to 1613 TFLOP/s forward (71% of 2.25 PFLOP/s) on B200, BF16 -- other hardware, context only"
 
@@ -174,6 +174,7 @@ def main():
     f_dkdv = 2.0 * pairs * (2 * w.dqk + 2 * w.dv)     # S, dK contract/emit d_qk; dP, dV d_v
     f_dq = 2.0 * pairs * (2 * w.dqk + w.dv)           # S, dQ over d_qk; dP over d_v
     tf = lambda flops, ms: flops / ms / 1e9
+    dkdv_name = "attn_bwd_dkdv_ws_kernel" if w.dqk == 128 else "attn_bwd_dkdv_kernel"
     out = {
         "metric": "attention fwd / bwd TFLOPs/s (bf16) and % of MI355X dense BF16 MFMA peak",
         "value": round(tf(f_fwd + f_bwd, ms_step), 2), "unit": "TFLOP/s",
@@ -188,12 +189,13 @@ def main():
         "bwd": {"ms": round(ms_bwd, 4), "tflops": round(tf(f_bwd, ms_bwd), 1),
                 "frac_of_peak": round(tf(f_bwd, ms_bwd) / PEAK_BF16_TFLOPS, 4),
                 "ms_prepare": round(ms_prep, 4), "ms_dkdv": round(ms_dkdv, 4), "ms_dq": round(ms_dq, 4)},
-        # dominant kernel = attn_bwd_dkdv_kernel.  Its ALGORITHMIC work is what it executes on the
-        # MFMA units: four contractions (S, dP, dV, dK) of N^2 (d_qk or d_v) multiply-adds each.
-        "roofline": {"kernel": "attn_bwd_dkdv_kernel", "bound": "mfma",
+        # dominant kernel = the dK/dV kernel (wave-specialised variant at d_qk = 128).  Its ALGORITHMIC
+        # work is what it executes on the MFMA units: four contractions (S, dP, dV, dK) of
+        # N^2 (d_qk or d_v) multiply-adds each.
+        "roofline": {"kernel": dkdv_name, "bound": "mfma",
                      "achieved": round(tf(f_dkdv, ms_dkdv), 1), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                      "frac": round(tf(f_dkdv, ms_dkdv) / PEAK_BF16_TFLOPS, 4),
-                     "traffic": MEASURED_TRAFFIC.get(w.name, {}).get("attn_bwd_dkdv_kernel")},
+                     "traffic": MEASURED_TRAFFIC.get(w.name, {}).get(dkdv_name)},
         "roofline_dq": {"kernel": "attn_bwd_dq_kernel", "bound": "mfma",
                         "achieved": round(tf(f_dq, ms_dq), 1), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                         "frac": round(tf(f_dq, ms_dq) / PEAK_BF16_TFLOPS, 4),
