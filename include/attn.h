@@ -112,6 +112,15 @@ enum { ATTN_EXP2_RATE_BLOCKS = 2048 };
 int attn_exp2_emulated(const float* x, float* y, size_t n, int degree, void* stream);
 long long attn_exp2_rate(float* out, int degree, int iters, void* stream);
 
+/* Matrix-core ceiling probe (measurement only, like the two above): enqueues a kernel of
+ * ATTN_MFMA_RATE_BLOCKS x 512 threads (two waves per SIMD on 256 CUs) that issues nothing but
+ * v_mfma_f32_32x32x16_bf16 on register operands, 32 x iters per wave, with constant operands
+ * (random_operands = 0) or N(0,1)-like ones (!= 0: the data the attention workloads of paper
+ * Sec. 5 use).  out: device, ATTN_MFMA_RATE_BLOCKS * 512 floats.  Returns the number of FLOPs
+ * enqueued (> 0) or a negative error code; the caller times it on the stream. */
+enum { ATTN_MFMA_RATE_BLOCKS = 256 };
+long long attn_mfma_rate(float* out, int random_operands, int iters, void* stream);
+
 /* Human-readable text for a return code (static storage). */
 const char* attn_strerror(int code);
 

@@ -51,6 +51,8 @@ def lib():
         L.attn_exp2_emulated.restype = i
         L.attn_exp2_rate.argtypes = [vp, i, i, vp]
         L.attn_exp2_rate.restype = ctypes.c_longlong
+        L.attn_mfma_rate.argtypes = [vp, i, i, vp]
+        L.attn_mfma_rate.restype = ctypes.c_longlong
         L.attn_strerror.argtypes = [i]
         L.attn_strerror.restype = ctypes.c_char_p
         L.attn_version.restype = i
@@ -131,6 +133,21 @@ def attn_exp2_rate(degree, iters, out=None, stream=None):
     if out is None:
         out = torch.empty(ATTN_EXP2_RATE_BLOCKS * 256, dtype=torch.float32, device="cuda")
     n = lib().attn_exp2_rate(ctypes.c_void_p(out.data_ptr()), int(degree), int(iters), _stream(stream))
+    if n <= 0:
+        _check(int(n) or ATTN_EINVAL)
+    return int(n), out
+
+
+ATTN_MFMA_RATE_BLOCKS = 256
+
+
+def attn_mfma_rate(random_operands, iters, out=None, stream=None):
+    """Enqueue the pure-MFMA ceiling kernel; returns (FLOPs enqueued, out tensor)."""
+    import torch
+    if out is None:
+        out = torch.empty(ATTN_MFMA_RATE_BLOCKS * 512, dtype=torch.float32, device="cuda")
+    n = lib().attn_mfma_rate(ctypes.c_void_p(out.data_ptr()), int(bool(random_operands)), int(iters),
+                             _stream(stream))
     if n <= 0:
         _check(int(n) or ATTN_EINVAL)
     return int(n), out

@@ -64,9 +64,62 @@ __global__ void __launch_bounds__(256) exp2_rate_kernel(float* __restrict__ out,
     out[(size_t)blockIdx.x * 256 + threadIdx.x] = t;
 }
 
+// Matrix-core ceiling: nothing but v_mfma_f32_32x32x16_bf16 on register operands, two waves per
+// SIMD, four accumulation chains per wave.  With random operands the chip's power management
+// lowers the shader clock; the rate this kernel sustains is what any bf16 MFMA kernel on such
+// data is bounded by, whatever its instruction stream.
+__device__ __forceinline__ float hash_gauss(uint32_t s)   // sum of four uniforms, variance 1
+{
+    float acc = 0.f;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        s = s * 1664525u + 1013904223u; s ^= s >> 15; s *= 2246822519u; s ^= s >> 13;
+        acc += (float)(s >> 8) * (1.0f / 16777216.0f);
+    }
+    return (acc - 2.0f) * 1.7320508f;
+}
+
+__global__ void __launch_bounds__(512) mfma_rate_kernel(float* __restrict__ out, int iters, int random_operands)
+{
+    typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+    typedef __attribute__((ext_vector_type(16))) float f32x16;
+    bf16x8 a[8], b[8];
+#pragma unroll
+    for (int f = 0; f < 8; ++f)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const uint32_t id = ((blockIdx.x * 512 + threadIdx.x) * 8 + f) * 8 + e;
+            a[f][e] = (__bf16)(random_operands ? hash_gauss(id) : 1.0f);
+            b[f][e] = (__bf16)(random_operands ? hash_gauss(id + 0x9e3779b9u) : 0.5f);
+        }
+    f32x16 c[4] = {{0}, {0}, {0}, {0}};
+    for (int i = 0; i < iters; ++i) {
+#pragma unroll
+        for (int m = 0; m < 32; ++m)
+            c[m % 4] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[m % 8], b[(m / 4) % 8], c[m % 4], 0, 0, 0);
+        if ((i & 255) == 255) {   // keep the accumulators finite
+#pragma unroll
+            for (int m = 0; m < 4; ++m)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) c[m][r] *= 1e-6f;
+        }
+    }
+    out[(size_t)blockIdx.x * 512 + threadIdx.x] = c[0][0] + c[1][1] + c[2][2] + c[3][3];
+}
+
 }  // namespace attn
 
 extern "C" {
+
+long long attn_mfma_rate(float* out, int random_operands, int iters, void* stream)
+{
+    using namespace attn;
+    if (!out || iters <= 0) return ATTN_EINVAL;
+    if (launch_kernel(mfma_rate_kernel, dim3(ATTN_MFMA_RATE_BLOCKS), dim3(512), 0, stream, out, iters,
+                      random_operands) != hipSuccess)
+        return ATTN_ELAUNCH;
+    return (long long)ATTN_MFMA_RATE_BLOCKS * 8 * iters * 32 * (2LL * 32 * 32 * 16);
+}
 
 int attn_exp2_emulated(const float* x, float* y, size_t n, int degree, void* stream)
 {

@@ -71,3 +71,28 @@ def test_emulation_is_slower_than_the_hardware_instruction(capsys):
     with open(path, "w") as f:
         f.write("degree (0 = v_exp_f32) : T evaluations / s\n" + "\n".join(f"{k} : {v:.3f}" for k, v in rates.items()) + "\n")
     assert rates[3] < rates[0] and rates[4] < rates[0] and rates[5] < rates[0]
+
+
+def test_matrix_core_ceiling_on_random_operands():
+    """Pure-MFMA rate with constant and with N(0,1) operands: the second is the ceiling every bf16
+    MFMA kernel on such data is bounded by (the power limit lowers the clock)."""
+    import paper_2603_05451_amd as A
+    rates = {}
+    for name, rnd in (("constant", 0), ("N(0,1)", 1)):
+        A.attn_mfma_rate(rnd, 2000)
+        best = 0.0
+        for _ in range(2):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            flops, out = A.attn_mfma_rate(rnd, 40000)      # about 40-50 ms: long enough for the clock to settle
+            e1.record()
+            e1.synchronize()
+            assert torch.isfinite(out).all()
+            best = max(best, flops / (e0.elapsed_time(e1) * 1e-3) / 1e12)
+        rates[name] = best
+    print("pure MFMA TFLOP/s:", {k: round(v) for k, v in rates.items()})
+    path = os.path.join(os.path.dirname(os.path.dirname(__file__)), "gpurun_out", "mfma_rates.txt")
+    os.makedirs(os.path.dirname(path), exist_ok=True)
+    with open(path, "w") as f:
+        f.write("\n".join(f"{k} operands : {v:.0f} TFLOP/s" for k, v in rates.items()) + "\n")
+    assert 1000 < rates["N(0,1)"] <= rates["constant"] * 1.02 < 2600
