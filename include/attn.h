@@ -85,7 +85,7 @@ int attn_bwd_ex(const void* q, const void* k, const void* v, const void* o, cons
 
 /* attn_bwd_ex restricted to a subset of its three kernels, for per-kernel timing and
  * profiling (the backward of paper Sec. 3.2 is one logical step; this splits it at the
- * kernel boundaries).  phases is a bit mask: ATTN_BWD_PREPARE (D and base-2 LSE into the
+ * kernel boundaries).  phases is a bit mask: ATTN_BWD_PREPARE (-D and base-2 LSE into the
  * workspace), ATTN_BWD_DKDV (writes dk, dv), ATTN_BWD_DQ (writes dq).  All arguments as
  * attn_bwd_ex.  ATTN_BWD_DKDV and ATTN_BWD_DQ read what ATTN_BWD_PREPARE left in the
  * workspace and are independent of each other. */

@@ -5,8 +5,8 @@
 //
 // Three kernels:
 //   bwd_prepare : D_i = sum_c dO_ic O_ic (the identity sum_j P_ij dP_ij = dO_i . O_i that
-//                 follows from the softmax Jacobian of Sec. 2.1) and LSE in base-2 units.
-//                 HBM bound.
+//                 follows from the softmax Jacobian of Sec. 2.1), stored as -D_i, and LSE in
+//                 base-2 units.  HBM bound.
 //   bwd_dkdv    : one workgroup per KV tile looping over query tiles, dK and dV accumulated
 //                 on chip for the whole loop (the loop structure of paper Sec. 3.2.2).
 //   bwd_dq      : one workgroup per query tile looping over KV tiles, dQ accumulated on chip.
@@ -67,7 +67,7 @@ bwd_prepare_kernel(const bf16* __restrict__ o, const bf16* __restrict__ d_o, con
         const int64_t b = bi / N;
         const int i = (int)(bi - b * N);
         const int64_t idx = (b * H + h) * N + i;
-        D[idx] = acc;
+        D[idx] = -acc;           // stored negated: the consumers add it (or start an accumulator from it)
         lse2[idx] = lse[idx] * kLog2e;
     }
 }
@@ -248,7 +248,7 @@ attn_bwd_dkdv_kernel(const bf16* __restrict__ q, const bf16* __restrict__ k, con
                     const int r = 4 * r4 + e;
                     float p = fast_exp2(fmaf(s[r], scale_log2e, -L[e]));
                     if (diag && (kw0 + c > q0 + 32 * qb + 8 * r4 + 4 * h + e)) p = 0.f;
-                    const float ds = p * (dp[r] - Dr[e]);
+                    const float ds = p * (dp[r] + Dr[e]);      // Dr holds -D
                     pb[r >> 3][r & 7] = (bf16)p;
                     dsb[r >> 3][r & 7] = (bf16)ds;
                 }
@@ -431,25 +431,34 @@ attn_bwd_dkdv_ws_kernel(const bf16* __restrict__ q, const bf16* __restrict__ k, 
                     for (int t = 0; t < GRP; ++t) {
                         const int st = g * GRP + t;
                         if (st < KSQ) s[qb] = mfma32(fr[g & 1][t], kf[st], st == 0 ? f32x16{} : s[qb]);
-                        else dp[qb] = mfma32(fr[g & 1][t], vf[st - KSQ], st == KSQ ? f32x16{} : dp[qb]);
+                        else dp[qb] = mfma32(fr[g & 1][t], vf[st - KSQ], dp[qb]);   // starts from -D
                     }
                 };
-                // LSE and D of the 4 query rows of register group r4: one 16-byte broadcast read
-                // each, fetched one group ahead of its use
-                f32x4 Lq[2], Dq[2];
+                // LSE of the 4 query rows of register group r4: one 16-byte broadcast read, fetched
+                // one group ahead of its use.  -D of the same rows is read straight into the dP
+                // accumulator (register r of the accumulator is query row 8(r/4) + 4h + r%4), so
+                // the MFMAs deliver dP - D.
+                f32x4 Lq[2];
                 auto load_stats = [&](int qb, int r4) {
                     Lq[r4 & 1] = *(const ATTN_LDS f32x4*)(stp + (32 * qb + 8 * r4) * 4);
-                    Dq[r4 & 1] = *(const ATTN_LDS f32x4*)(stp + (64 + 32 * qb + 8 * r4) * 4);
+                };
+                auto load_negD = [&](int qb) {
+#pragma unroll
+                    for (int r4 = 0; r4 < 4; ++r4) {
+                        const f32x4 nd = *(const ATTN_LDS f32x4*)(stp + (64 + 32 * qb + 8 * r4) * 4);
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) dp[qb][4 * r4 + e] = nd[e];
+                    }
                 };
                 // P = 2^(c S - LSE2), dS = P o (dP - D) for register group r4 of block qb
                 auto elementwise = [&](int qb, int r4) {
-                    const f32x4 L = Lq[r4 & 1], Dr = Dq[r4 & 1];
+                    const f32x4 L = Lq[r4 & 1];
 #pragma unroll
                     for (int e = 0; e < 4; ++e) {
                         const int r = 4 * r4 + e;
                         float p = fast_exp2(fmaf(s[qb][r], scale_log2e, -L[e]));
                         if (diag && (kw0 + c > q0 + 32 * qb + 8 * r4 + 4 * h + e)) p = 0.f;
-                        const float ds = p * (dp[qb][r] - Dr[e]);
+                        const float ds = p * dp[qb][r];
                         pb[qb][r >> 3][r & 7] = (bf16)p;
                         dsb[qb][r >> 3][r & 7] = (bf16)ds;
                     }
@@ -462,6 +471,7 @@ attn_bwd_dkdv_ws_kernel(const bf16* __restrict__ q, const bf16* __restrict__ k, 
                         if (qb < QB) {
                             if (g + 1 < NG) load_a(qb, g + 1, fr[(g + 1) & 1]);
                             else if (qb + 1 < QB) load_a(qb + 1, 0, fr[(g + 1) & 1]);
+                            if (g == 0) load_negD(qb);         // wanted by the first dP MFMA, two groups on
                         }
                         // statistics for the elementwise group after this one
                         if (g + 1 < NG) { if (qb > 0) load_stats(qb - 1, g + 1); }
@@ -790,7 +800,7 @@ attn_bwd_dq_kernel(const bf16* __restrict__ q, const bf16* __restrict__ k, const
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
                 const float p = fast_exp2(fmaf(s[r], scale_log2e, -lse_q));
-                dsf[kb][r >> 3][r & 7] = (bf16)(p * (dp[r] - D_q));
+                dsf[kb][r >> 3][r & 7] = (bf16)(p * (dp[r] + D_q));      // D_q holds -D
             }
         }
 

@@ -23,7 +23,7 @@ struct BwdArgs {
     int B, H, Hkv, N, d_qk, d_v;
     float scale;
     int causal;
-    // workspace carved up by the API: D = rowsum(dO o O) and the base-2 LSE
+    // workspace carved up by the API: -D = -rowsum(dO o O) and the base-2 LSE
     float* D;
     float* lse2;
     void* stream;
