@@ -99,6 +99,27 @@ int attn_bwd_phases(const void* q, const void* k, const void* v, const void* o, 
  * D and the base-2 LSE, [B,H,N] fp32 each (256-byte aligned sections). */
 size_t attn_bwd_workspace_bytes(int B, int H, int Hkv, int N, int d_qk, int d_v);
 
+/* Variable sequence lengths (paper Sec. 3.3): B sequences of different lengths packed back to
+ * back, self-attention inside each sequence only.
+ *   layouts  q, o, d_o, dq : [T, H, d]    k, dk : [T, Hkv, d_qk]    v, dv : [T, Hkv, d_v]   bf16
+ *            lse           : [H, T] fp32
+ *            cu_seqlens    : [B + 1] int32, DEVICE memory, cu[0] = 0, non-decreasing,
+ *                            cu[B] = T = total_tokens; sequence b owns rows cu[b] .. cu[b+1]-1.
+ *                            Any length >= 0 is allowed (no multiple-of-128 requirement).
+ *   causal != 0: inside a sequence, key j is visible to query i iff j <= i.
+ *   The host never reads cu_seqlens: a small kernel turns it into a table of 128-row tiles,
+ *   sequences with the most tiles first (the longest-processing-time-first order of Sec. 3.3),
+ *   and the attention kernels are launched over an upper bound of T/128 + B tiles per head.
+ *   workspace: attn_varlen_workspace_bytes(..., backward) bytes, 256-byte aligned; the forward
+ *   call needs the backward = 0 size, the backward call the backward = 1 size.  Contents on entry
+ *   are ignored.  All other conventions (device pointers, stream, alignment, head dims, error
+ *   codes, nothing enqueued on error) are those of attn_fwd_ex / attn_bwd_ex.  Behaviour is
+ *   undefined if cu_seqlens violates the conditions above. */
+size_t attn_varlen_workspace_bytes(int B, int total_tokens, int H, int Hkv, int d_qk, int d_v, int backward);
+int attn_varlen_fwd(const void* q, const void* k, const void* v, void* o, float* lse,
+                    const int* cu_seqlens, int B, int total_tokens, int H, int Hkv, int d_qk, int d_v,
+                    float scale, int causal, void* workspace, size_t workspace_bytes, void* stream);
+
 /* Software 2^x of paper Sec. 3.1.3 (range reduction + degree-n minimax polynomial, p0 = 1, Horner
  * with FMAs, exponent splice), provided to measure it on this hardware; attn_fwd does not use
  * it (v_exp_f32 and the FMAs share one issue port on CDNA4, so emulation cannot add throughput).

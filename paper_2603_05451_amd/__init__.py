@@ -47,6 +47,10 @@ def lib():
         L.attn_bwd_phases.restype = i
         L.attn_bwd_workspace_bytes.argtypes = [i] * 6
         L.attn_bwd_workspace_bytes.restype = sz
+        L.attn_varlen_workspace_bytes.argtypes = [i] * 7
+        L.attn_varlen_workspace_bytes.restype = sz
+        L.attn_varlen_fwd.argtypes = [vp] * 6 + [i, i, i, i, i, i, f, i, vp, sz, vp]
+        L.attn_varlen_fwd.restype = i
         L.attn_exp2_emulated.argtypes = [vp, vp, sz, i, vp]
         L.attn_exp2_emulated.restype = i
         L.attn_exp2_rate.argtypes = [vp, i, i, vp]
@@ -109,6 +113,41 @@ def attn_fwd(q, k, v, scale, causal, o=None, lse=None, stream=None):
                            _dev_bf16(v, "v", (B, N, Hkv, dv)), _dev_bf16(o, "o", (B, N, H, dv)),
                            ctypes.c_void_p(lse.data_ptr()), B, H, Hkv, N, dqk, dv,
                            float(scale), int(bool(causal)), _stream(stream))
+    _check(rc)
+    return o, lse
+
+
+def attn_varlen_workspace_bytes(B, total_tokens, H, Hkv, d_qk, d_v, backward) -> int:
+    return int(lib().attn_varlen_workspace_bytes(B, total_tokens, H, Hkv, d_qk, d_v, int(bool(backward))))
+
+
+def _dev_cu(cu, B):
+    import torch
+    if not (cu.is_cuda and cu.dtype == torch.int32 and cu.is_contiguous() and tuple(cu.shape) == (B + 1,)):
+        raise ValueError("cu_seqlens must be a contiguous int32 CUDA tensor [B+1]")
+    return ctypes.c_void_p(cu.data_ptr())
+
+
+def attn_varlen_fwd(q, k, v, cu_seqlens, scale, causal, o=None, lse=None, workspace=None, stream=None):
+    """Packed variable-length batch: q [T,H,d_qk], k [T,Hkv,d_qk], v [T,Hkv,d_v] bf16, cu_seqlens [B+1]
+    int32, all on the GPU -> (o [T,H,d_v] bf16, lse [H,T] fp32)."""
+    import torch
+    T, H, dqk = q.shape
+    Hkv, dv = k.shape[1], v.shape[2]
+    B = cu_seqlens.numel() - 1
+    if o is None:
+        o = torch.empty((T, H, dv), dtype=torch.bfloat16, device=q.device)
+    if lse is None:
+        lse = torch.empty((H, T), dtype=torch.float32, device=q.device)
+    if not (lse.is_cuda and lse.dtype == torch.float32 and lse.is_contiguous() and tuple(lse.shape) == (H, T)):
+        raise ValueError("lse must be a contiguous fp32 CUDA tensor [H,T]")
+    need = attn_varlen_workspace_bytes(B, T, H, Hkv, dqk, dv, False)
+    if workspace is None:
+        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=q.device)
+    rc = lib().attn_varlen_fwd(_dev_bf16(q, "q"), _dev_bf16(k, "k", (T, Hkv, dqk)), _dev_bf16(v, "v", (T, Hkv, dv)),
+                               _dev_bf16(o, "o", (T, H, dv)), ctypes.c_void_p(lse.data_ptr()), _dev_cu(cu_seqlens, B),
+                               B, T, H, Hkv, dqk, dv, float(scale), int(bool(causal)),
+                               ctypes.c_void_p(workspace.data_ptr()), workspace.numel(), _stream(stream))
     _check(rc)
     return o, lse
 

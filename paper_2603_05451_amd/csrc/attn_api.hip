@@ -115,6 +115,69 @@ int attn_bwd(const void* q, const void* k, const void* v, const void* o, const v
                        workspace, workspace_bytes, stream);
 }
 
+// ---------------------------------------------------------------------------------------------
+// variable-length entry points
+
+namespace {
+
+int check_varlen(int B, int T, int H, int Hkv, int d_qk, int d_v)
+{
+    if (B <= 0 || T <= 0 || H <= 0 || Hkv <= 0) return ATTN_EINVAL;
+    if (H % Hkv != 0) return ATTN_EINVAL;
+    if (!dims_supported(d_qk, d_v)) return ATTN_EUNSUPPORTED;
+    if (((int64_t)T / 128 + B) * H > 0x7fffffffLL) return ATTN_EUNSUPPORTED;
+    if ((int64_t)H * (d_qk > d_v ? d_qk : d_v) * 2 * 128 > 0x7fffffffLL) return ATTN_EUNSUPPORTED;
+    return ATTN_OK;
+}
+
+struct VarlenLayout {
+    int max_tiles;
+    size_t plan_off, d_off, lse2_off, total_fwd, total_bwd;
+};
+
+VarlenLayout varlen_layout(int B, int T, int H)
+{
+    VarlenLayout w;
+    w.max_tiles = T / 128 + B;          // sum over sequences of ceil(len / 128) never exceeds this
+    w.plan_off = 0;
+    w.total_fwd = align_up((size_t)w.max_tiles * 16, 256);
+    w.d_off = w.total_fwd;
+    w.lse2_off = w.d_off + align_up((size_t)H * T * sizeof(float), 256);
+    w.total_bwd = w.lse2_off + align_up((size_t)H * T * sizeof(float), 256);
+    return w;
+}
+
+}  // namespace
+
+size_t attn_varlen_workspace_bytes(int B, int total_tokens, int H, int Hkv, int d_qk, int d_v, int backward)
+{
+    if (check_varlen(B, total_tokens, H, Hkv, d_qk, d_v) != ATTN_OK) return 0;
+    const VarlenLayout w = varlen_layout(B, total_tokens, H);
+    return backward ? w.total_bwd : w.total_fwd;
+}
+
+int attn_varlen_fwd(const void* q, const void* k, const void* v, void* o, float* lse,
+                    const int* cu_seqlens, int B, int total_tokens, int H, int Hkv, int d_qk, int d_v,
+                    float scale, int causal, void* workspace, size_t workspace_bytes, void* stream)
+{
+    if (!q || !k || !v || !o || !lse || !cu_seqlens || !workspace) return ATTN_EINVAL;
+    if (int rc = check_varlen(B, total_tokens, H, Hkv, d_qk, d_v)) return rc;
+    if (!(scale > 0.0f) || !(scale < 1e30f)) return ATTN_EINVAL;
+    if (misaligned(q, 16) || misaligned(k, 16) || misaligned(v, 16) || misaligned(o, 16) ||
+        misaligned(lse, 4) || misaligned(cu_seqlens, 4) || misaligned(workspace, 256))
+        return ATTN_EINVAL;
+    const VarlenLayout w = varlen_layout(B, total_tokens, H);
+    if (workspace_bytes < w.total_fwd) return ATTN_EINVAL;
+    char* ws = static_cast<char*>(workspace);
+    if (attn::launch_varlen_plan(cu_seqlens, B, ws + w.plan_off, w.max_tiles, stream) != 0) return ATTN_ELAUNCH;
+    attn::FwdArgs a{q, k, v, o, lse, B, H, Hkv, 0, d_qk, d_v, scale, causal != 0, stream};
+    a.plan = ws + w.plan_off;
+    a.T = total_tokens;
+    a.max_tiles = w.max_tiles;
+    const int rc = attn::launch_fwd(a);
+    return rc == 0 ? ATTN_OK : (rc == -2 ? ATTN_EUNSUPPORTED : ATTN_ELAUNCH);
+}
+
 const char* attn_strerror(int code)
 {
     switch (code) {

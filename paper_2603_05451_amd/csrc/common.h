@@ -170,6 +170,30 @@ struct TileCopy {
 #pragma unroll
         for (int t = 0; t < N; ++t) issue(t, gtile, lds_tile);
     }
+    // The same copy for a tile of which only the first `valid_rows` (>= 1) rows exist: every
+    // later row re-reads the last valid one, so nothing outside the tensor is touched.  Per-lane
+    // address arithmetic; meant for the one ragged tile at the end of a sequence.  `tid` and the
+    // row stride must be those given to init.
+    __device__ __forceinline__ void issue_all_guarded(const bf16* gtile, ATTN_LDS char* lds_tile,
+                                                      int valid_rows, int64_t gstride, int tid) const
+    {
+        constexpr int CPR = D / 8;
+        const int wave = tid >> 6, lane = tid & 63;
+        const uint32_t row_bytes = (uint32_t)gstride * 2u;
+#pragma unroll
+        for (int t = 0; t < N; ++t) {
+            const int row = ((t * (NT / 64) + wave) * 64 + lane) / CPR;
+            const int over = row - (valid_rows - 1);
+            const uint32_t off = goff[t] - (over > 0 ? (uint32_t)over * row_bytes : 0u);
+            const uint32_t m0 = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)lds_tile) + loff[t];
+            const uint64_t base = (uint64_t)gtile;
+            const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)base);
+            const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)(base >> 32));
+            const uint64_t sbase = ((uint64_t)hi << 32) | lo;
+            asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                         :: "s"(m0), "v"(off), "s"(sbase) : "memory");
+        }
+    }
 };
 
 // Compile-time loop: f(std::integral_constant<int, I>) for I = 0 .. N-1.

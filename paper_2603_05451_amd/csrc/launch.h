@@ -14,6 +14,10 @@ struct FwdArgs {
     float scale;
     int causal;
     void* stream;
+    // variable-length mode (plan != nullptr): B and N unused, T = total tokens, max_tiles = size
+    // of the plan table (an upper bound on the number of 128-row tiles)
+    const void* plan = nullptr;
+    int T = 0, max_tiles = 0;
 };
 
 struct BwdArgs {
@@ -28,6 +32,8 @@ struct BwdArgs {
     float* lse2;
     void* stream;
     int phases;   // bit mask: 1 prepare, 2 dK/dV kernel, 4 dQ kernel
+    const void* plan = nullptr;   // variable-length mode, as in FwdArgs
+    int T = 0, max_tiles = 0;
 };
 
 // Launch through hipLaunchKernel so that the status returned belongs to THIS launch (the
@@ -46,5 +52,7 @@ inline hipError_t launch_kernel(void (*kern)(KArgs...), dim3 grid, dim3 block, s
 // 0 on success, -2 unsupported head dims, -3 launch failure.
 int launch_fwd(const FwdArgs& a);
 int launch_bwd(const BwdArgs& a);
+// Fills the plan table of the variable-length entry points on the device: 0 or -3.
+int launch_varlen_plan(const int* cu_seqlens, int B, void* plan, int max_tiles, void* stream);
 
 }  // namespace attn
