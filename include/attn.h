@@ -119,6 +119,14 @@ size_t attn_varlen_workspace_bytes(int B, int total_tokens, int H, int Hkv, int 
 int attn_varlen_fwd(const void* q, const void* k, const void* v, void* o, float* lse,
                     const int* cu_seqlens, int B, int total_tokens, int H, int Hkv, int d_qk, int d_v,
                     float scale, int causal, void* workspace, size_t workspace_bytes, void* stream);
+/* Backward of attn_varlen_fwd (paper Sec. 2.1 second display, per sequence): o and lse must be that
+ * call's outputs for the same arguments; dk and dv are summed over the query heads of each group.
+ * Rows of dq, dk, dv that belong to no sequence do not exist (T = cu[B]); every existing row is
+ * written.  No atomics: bit-reproducible like attn_bwd. */
+int attn_varlen_bwd(const void* q, const void* k, const void* v, const void* o, const void* d_o,
+                    const float* lse, void* dq, void* dk, void* dv,
+                    const int* cu_seqlens, int B, int total_tokens, int H, int Hkv, int d_qk, int d_v,
+                    float scale, int causal, void* workspace, size_t workspace_bytes, void* stream);
 
 /* Software 2^x of paper Sec. 3.1.3 (range reduction + degree-n minimax polynomial, p0 = 1, Horner
  * with FMAs, exponent splice), provided to measure it on this hardware; attn_fwd does not use

@@ -51,6 +51,8 @@ def lib():
         L.attn_varlen_workspace_bytes.restype = sz
         L.attn_varlen_fwd.argtypes = [vp] * 6 + [i, i, i, i, i, i, f, i, vp, sz, vp]
         L.attn_varlen_fwd.restype = i
+        L.attn_varlen_bwd.argtypes = [vp] * 10 + [i, i, i, i, i, i, f, i, vp, sz, vp]
+        L.attn_varlen_bwd.restype = i
         L.attn_exp2_emulated.argtypes = [vp, vp, sz, i, vp]
         L.attn_exp2_emulated.restype = i
         L.attn_exp2_rate.argtypes = [vp, i, i, vp]
@@ -150,6 +152,31 @@ def attn_varlen_fwd(q, k, v, cu_seqlens, scale, causal, o=None, lse=None, worksp
                                ctypes.c_void_p(workspace.data_ptr()), workspace.numel(), _stream(stream))
     _check(rc)
     return o, lse
+
+
+def attn_varlen_bwd(q, k, v, o, d_o, lse, cu_seqlens, scale, causal, dq=None, dk=None, dv=None, workspace=None,
+                    stream=None):
+    """Backward of attn_varlen_fwd: returns (dq [T,H,d_qk], dk [T,Hkv,d_qk], dv [T,Hkv,d_v]) bf16."""
+    import torch
+    T, H, dqk = q.shape
+    Hkv, dv_ = k.shape[1], v.shape[2]
+    B = cu_seqlens.numel() - 1
+    dq = torch.empty_like(q) if dq is None else dq
+    dk = torch.empty_like(k) if dk is None else dk
+    dv = torch.empty_like(v) if dv is None else dv
+    need = attn_varlen_workspace_bytes(B, T, H, Hkv, dqk, dv_, True)
+    if workspace is None:
+        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=q.device)
+    if not (lse.is_cuda and lse.dtype == torch.float32 and lse.is_contiguous() and tuple(lse.shape) == (H, T)):
+        raise ValueError("lse must be a contiguous fp32 CUDA tensor [H,T]")
+    rc = lib().attn_varlen_bwd(_dev_bf16(q, "q"), _dev_bf16(k, "k", (T, Hkv, dqk)), _dev_bf16(v, "v", (T, Hkv, dv_)),
+                               _dev_bf16(o, "o", (T, H, dv_)), _dev_bf16(d_o, "d_o", (T, H, dv_)),
+                               ctypes.c_void_p(lse.data_ptr()), _dev_bf16(dq, "dq", (T, H, dqk)),
+                               _dev_bf16(dk, "dk", (T, Hkv, dqk)), _dev_bf16(dv, "dv", (T, Hkv, dv_)),
+                               _dev_cu(cu_seqlens, B), B, T, H, Hkv, dqk, dv_, float(scale), int(bool(causal)),
+                               ctypes.c_void_p(workspace.data_ptr()), workspace.numel(), _stream(stream))
+    _check(rc)
+    return dq, dk, dv
 
 
 ATTN_EXP2_RATE_BLOCKS = 2048

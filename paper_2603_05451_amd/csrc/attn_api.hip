@@ -178,6 +178,32 @@ int attn_varlen_fwd(const void* q, const void* k, const void* v, void* o, float*
     return rc == 0 ? ATTN_OK : (rc == -2 ? ATTN_EUNSUPPORTED : ATTN_ELAUNCH);
 }
 
+int attn_varlen_bwd(const void* q, const void* k, const void* v, const void* o, const void* d_o,
+                    const float* lse, void* dq, void* dk, void* dv,
+                    const int* cu_seqlens, int B, int total_tokens, int H, int Hkv, int d_qk, int d_v,
+                    float scale, int causal, void* workspace, size_t workspace_bytes, void* stream)
+{
+    if (!q || !k || !v || !o || !d_o || !lse || !dq || !dk || !dv || !cu_seqlens || !workspace) return ATTN_EINVAL;
+    if (int rc = check_varlen(B, total_tokens, H, Hkv, d_qk, d_v)) return rc;
+    if (!(scale > 0.0f) || !(scale < 1e30f)) return ATTN_EINVAL;
+    const void* ptrs[] = {q, k, v, o, d_o, dq, dk, dv};
+    for (const void* p : ptrs)
+        if (misaligned(p, 16)) return ATTN_EINVAL;
+    if (misaligned(lse, 4) || misaligned(cu_seqlens, 4) || misaligned(workspace, 256)) return ATTN_EINVAL;
+    const VarlenLayout w = varlen_layout(B, total_tokens, H);
+    if (workspace_bytes < w.total_bwd) return ATTN_EINVAL;
+    char* ws = static_cast<char*>(workspace);
+    if (attn::launch_varlen_plan(cu_seqlens, B, ws + w.plan_off, w.max_tiles, stream) != 0) return ATTN_ELAUNCH;
+    attn::BwdArgs a{q, k, v, o, d_o, lse, dq, dk, dv, B, H, Hkv, 0, d_qk, d_v, scale, causal != 0,
+                    reinterpret_cast<float*>(ws + w.d_off), reinterpret_cast<float*>(ws + w.lse2_off),
+                    stream, ATTN_BWD_ALL};
+    a.plan = ws + w.plan_off;
+    a.T = total_tokens;
+    a.max_tiles = w.max_tiles;
+    const int rc = attn::launch_bwd(a);
+    return rc == 0 ? ATTN_OK : (rc == -2 ? ATTN_EUNSUPPORTED : ATTN_ELAUNCH);
+}
+
 const char* attn_strerror(int code)
 {
     switch (code) {

@@ -72,235 +72,12 @@ bwd_prepare_kernel(const bf16* __restrict__ o, const bf16* __restrict__ d_o, con
     }
 }
 
-// ------------------------------------------------------------------------------------------
-// bwd_dkdv: block = 4 waves = 128 keys (32 per wave); query tiles of 64 rows stream through
-// LDS (double buffered, direct global->LDS copies).
-template <int DQK, int DV, bool CAUSAL>
-__global__ void __launch_bounds__(BWD_NT, (DQK <= 64 ? 2 : 1))
-attn_bwd_dkdv_kernel(const bf16* __restrict__ q, const bf16* __restrict__ k, const bf16* __restrict__ v,
-                     const bf16* __restrict__ d_o, const float* __restrict__ lse2, const float* __restrict__ D,
-                     bf16* __restrict__ dk, bf16* __restrict__ dv,
-                     int H, int Hkv, int N, float scale, float scale_log2e)
-{
-    constexpr int KSQ = DQK / 16, KSV = DV / 16;       // k-steps over the head dims
-    constexpr int DBQ = DQK / 32, DBV = DV / 32;       // 32-wide head-dim blocks
-    constexpr int QB = BWD_BQ / 32;                    // 32-query blocks per step (2)
-    constexpr int Q_BYTES = BWD_BQ * DQK * 2;
-    constexpr int DO_BYTES = BWD_BQ * DV * 2;
-
-    extern __shared__ __attribute__((aligned(1024))) char smem_raw[];
-    ATTN_LDS char* smem = (ATTN_LDS char*)smem_raw;
-    ATTN_LDS char* q_lds[2] = {smem, smem + Q_BYTES};
-    ATTN_LDS char* do_lds[2] = {smem + 2 * Q_BYTES, smem + 2 * Q_BYTES + DO_BYTES};
-    ATTN_LDS char* st_lds = smem + 2 * Q_BYTES + 2 * DO_BYTES;    // [2 buffers][lse2 | D][64] floats
-
-    const int tid = threadIdx.x;
-    const int wave = tid >> 6, lane = tid & 63;
-    const int c = lane & 31, h = lane >> 5;
-    const int i16 = lane & 15;
-    // lane-constant parts of transposing-read addresses (4 rows x 32 bytes per 16 lanes)
-    const int tr_row = i16 >> 2;                                    // + row base
-    const int tr_chunk = 2 * ((lane >> 4) & 1) + ((i16 & 3) >> 1);  // + 4 * (32-column block)
-    const int tr_half = (i16 & 1) * 8;
-
-    // ---- block -> (batch, kv head, kv tile); same XCD un-dealing as the forward kernel
-    const int ntk = N / BWD_BK;
-    const int total = gridDim.x;
-    int vid = blockIdx.x;
-    if ((total & 7) == 0) vid = (blockIdx.x & 7) * (total >> 3) + (blockIdx.x >> 3);
-    const int bkv = vid / ntk;
-    const int kt = vid - bkv * ntk;            // causal: tile 0 has the longest loop and comes first
-    const int b = bkv / Hkv, kvh = bkv - b * Hkv;
-    const int G = H / Hkv;
-    const int k0 = kt * BWD_BK;
-    const int kw0 = k0 + wave * 32;
-
-    const int64_t q_stride = (int64_t)H * DQK, o_stride = (int64_t)H * DV;
-    const int64_t k_stride = (int64_t)Hkv * DQK, v_stride = (int64_t)Hkv * DV;
-    const bf16* kg = k + ((int64_t)b * N * Hkv + kvh) * DQK;
-    const bf16* vg = v + ((int64_t)b * N * Hkv + kvh) * DV;
-
-    const int i_first = CAUSAL ? k0 / BWD_BQ : 0;     // first query tile that sees this KV tile
-    const int nq = N / BWD_BQ - i_first;
-    const int nsteps = G * nq;
-
-    TileCopy<BWD_BQ, DQK, BWD_NT> qcopy;
-    TileCopy<BWD_BQ, DV, BWD_NT> docopy;
-    qcopy.init(q_stride, tid);
-    docopy.init(o_stride, tid);
-    auto issue_loads = [&](int step, int buf) {
-        const int g = step / nq, i = i_first + (step - g * nq);
-        const int hq = kvh * G + g;
-        const int64_t row0 = (int64_t)b * N + (int64_t)i * BWD_BQ;
-        qcopy.issue_all(q + row0 * q_stride + (int64_t)hq * DQK, q_lds[buf]);
-        docopy.issue_all(d_o + row0 * o_stride + (int64_t)hq * DV, do_lds[buf]);
-        if (wave < 2) {   // 64 floats each of lse2 and D
-            const float* src = (wave == 0 ? lse2 : D) + ((int64_t)b * H + hq) * N + (int64_t)i * BWD_BQ + lane;
-            dma4(src, st_lds + buf * 512 + wave * 256);
-        }
-    };
-    issue_loads(0, 0);
-
-    // this wave's K and V rows as B operands: lane = key kw0 + c, dims 16*ks + 8h .. +7
-    bf16x8 kf[KSQ], vf[KSV];
-    {
-        const bf16* krow = kg + (int64_t)(kw0 + c) * k_stride + 8 * h;
-        const bf16* vrow = vg + (int64_t)(kw0 + c) * v_stride + 8 * h;
-#pragma unroll
-        for (int ks = 0; ks < KSQ; ++ks) kf[ks] = *(const bf16x8*)(krow + 16 * ks);
-#pragma unroll
-        for (int ks = 0; ks < KSV; ++ks) vf[ks] = *(const bf16x8*)(vrow + 16 * ks);
-#pragma unroll
-        for (int ks = 0; ks < KSQ; ++ks) pin_ready(kf[ks]);
-#pragma unroll
-        for (int ks = 0; ks < KSV; ++ks) pin_ready(vf[ks]);
-    }
-
-    f32x16 dk_acc[DBQ], dv_acc[DBV];
-#pragma unroll
-    for (int db = 0; db < DBQ; ++db)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) dk_acc[db][r] = 0.f;
-#pragma unroll
-    for (int db = 0; db < DBV; ++db)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) dv_acc[db][r] = 0.f;
-
-    // One query tile.  The buffer index is a compile-time constant in the unrolled-by-two loop
-    // below, so every LDS read address is "lane register + immediate".
-    auto q_step = [&](auto bufc, int step) {
-        const int buf = bufc;
-        wait_async_copies();
-        __syncthreads();           // tiles of this step visible; everyone is done with the previous ones
-        if (step + 1 < nsteps) issue_loads(step + 1, buf ^ 1);
-
-        const int i = i_first + step % nq;
-        const int q0 = i * BWD_BQ;
-        const bool diag = CAUSAL && (q0 < k0 + BWD_BK - 1);     // some (query, key) pair is masked
-
-#pragma unroll
-        for (int qb = 0; qb < QB; ++qb) {
-            if (CAUSAL && diag && (kw0 > q0 + 32 * qb + 31)) continue;   // block wholly above the diagonal
-
-            // ---- S = Q K_w^T and dP = dO V_w^T for 32 queries x 32 keys; LDS reads run one
-            // group of 4 fragments ahead of the MFMAs that consume them
-            f32x16 s, dp;
-#pragma unroll
-            for (int r = 0; r < 16; ++r) { s[r] = 0.f; dp[r] = 0.f; }
-            {
-                constexpr int GRP = 4, NS = KSQ + KSV, NG = NS / GRP;
-                static_assert(KSQ % GRP == 0 && KSV % GRP == 0, "k-steps must split into whole groups");
-                bf16x8 fr[2][GRP];
-                auto load_a = [&](int g, bf16x8* dst) {
-#pragma unroll
-                    for (int t = 0; t < GRP; ++t) {
-                        const int st = g * GRP + t;
-                        dst[t] = st < KSQ
-                            ? lds_read_b128(q_lds[buf] + tile_off<DQK>(32 * qb + c, 2 * st + h))
-                            : lds_read_b128(do_lds[buf] + tile_off<DV>(32 * qb + c, 2 * (st - KSQ) + h));
-                    }
-                };
-                load_a(0, fr[0]);
-#pragma unroll
-                for (int g = 0; g < NG; ++g) {
-                    if (g + 1 < NG) load_a(g + 1, fr[(g + 1) & 1]);
-                    sched_fence();
-#pragma unroll
-                    for (int t = 0; t < GRP; ++t) {
-                        const int st = g * GRP + t;
-                        if (st < KSQ) s = mfma32(fr[g & 1][t], kf[st], s);
-                        else dp = mfma32(fr[g & 1][t], vf[st - KSQ], dp);
-                    }
-                    sched_fence();
-                }
-            }
-
-            // transposed fragments of dO and Q for the first 16 queries: in flight during the
-            // elementwise work below
-            bf16x4 tfr[2][DBV + DBQ][2];
-            auto load_t = [&](int kk, bf16x4 (*dst)[2]) {
-                const int row_lo = 32 * qb + 16 * kk + 4 * h + tr_row;   // queries, order 8s + 4h + j
-#pragma unroll
-                for (int db = 0; db < DBV; ++db) {
-                    const ATTN_LDS char* base = do_lds[buf] + tr_half;
-                    dst[db][0] = lds_read_tr(base + tile_off<DV>(row_lo, 4 * db + tr_chunk));
-                    dst[db][1] = lds_read_tr(base + tile_off<DV>(row_lo + 8, 4 * db + tr_chunk));
-                }
-#pragma unroll
-                for (int db = 0; db < DBQ; ++db) {
-                    const ATTN_LDS char* base = q_lds[buf] + tr_half;
-                    dst[DBV + db][0] = lds_read_tr(base + tile_off<DQK>(row_lo, 4 * db + tr_chunk));
-                    dst[DBV + db][1] = lds_read_tr(base + tile_off<DQK>(row_lo + 8, 4 * db + tr_chunk));
-                }
-            };
-            load_t(0, tfr[0]);
-            sched_fence();
-
-            // ---- P = 2^(c S - LSE2), dS = P o (dP - D); the query index is the register row
-            bf16x8 pb[2], dsb[2];
-            const ATTN_LDS float* st = (const ATTN_LDS float*)(st_lds + buf * 512);
-#pragma unroll
-            for (int r4 = 0; r4 < 4; ++r4) {
-                const f32x4 L = *(const ATTN_LDS f32x4*)(st + 32 * qb + 8 * r4 + 4 * h);
-                const f32x4 Dr = *(const ATTN_LDS f32x4*)(st + 64 + 32 * qb + 8 * r4 + 4 * h);
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    const int r = 4 * r4 + e;
-                    float p = fast_exp2(fmaf(s[r], scale_log2e, -L[e]));
-                    if (diag && (kw0 + c > q0 + 32 * qb + 8 * r4 + 4 * h + e)) p = 0.f;
-                    const float ds = p * (dp[r] + Dr[e]);      // Dr holds -D
-                    pb[r >> 3][r & 7] = (bf16)p;
-                    dsb[r >> 3][r & 7] = (bf16)ds;
-                }
-            }
-
-            // ---- dV_w^T += dO^T P,  dK_w^T += Q^T dS   (contraction over these 32 queries)
-#pragma unroll
-            for (int kk = 0; kk < 2; ++kk) {
-                if (kk + 1 < 2) load_t(kk + 1, tfr[(kk + 1) & 1]);
-                sched_fence();
-#pragma unroll
-                for (int db = 0; db < DBV; ++db)
-                    dv_acc[db] = mfma32(cat4(tfr[kk & 1][db][0], tfr[kk & 1][db][1]), pb[kk], dv_acc[db]);
-#pragma unroll
-                for (int db = 0; db < DBQ; ++db)
-                    dk_acc[db] = mfma32(cat4(tfr[kk & 1][DBV + db][0], tfr[kk & 1][DBV + db][1]), dsb[kk],
-                                        dk_acc[db]);
-                sched_fence();
-            }
-        }
-    };
-    if constexpr (DQK <= 128) {
-        for (int step = 0; step < nsteps; step += 2) {   // nsteps is even: N/64 and the causal start are even
-            q_step(std::integral_constant<int, 0>{}, step);
-            q_step(std::integral_constant<int, 1>{}, step + 1);
-        }
-    } else {
-        for (int step = 0; step < nsteps; ++step) q_step(step & 1, step);
-    }
-
-    // ---- epilogue: dk = scale * dK, dv = dV; accumulators hold the transposes (dims x keys)
-    bf16* dkrow = dk + ((int64_t)b * N + kw0 + c) * k_stride + (int64_t)kvh * DQK;
-    bf16* dvrow = dv + ((int64_t)b * N + kw0 + c) * v_stride + (int64_t)kvh * DV;
-#pragma unroll
-    for (int db = 0; db < DBQ; ++db)
-#pragma unroll
-        for (int r4 = 0; r4 < 4; ++r4) {
-            bf16x4 out;
-#pragma unroll
-            for (int e = 0; e < 4; ++e) out[e] = (bf16)(dk_acc[db][4 * r4 + e] * scale);
-            *(bf16x4*)(dkrow + 32 * db + 8 * r4 + 4 * h) = out;
-        }
-#pragma unroll
-    for (int db = 0; db < DBV; ++db)
-#pragma unroll
-        for (int r4 = 0; r4 < 4; ++r4) {
-            bf16x4 out;
-#pragma unroll
-            for (int e = 0; e < 4; ++e) out[e] = (bf16)dv_acc[db][4 * r4 + e];
-            *(bf16x4*)(dvrow + 32 * db + 8 * r4 + 4 * h) = out;
-        }
-}
+#define ATTN_VARLEN 0
+#include "attn_bwd_dkdv_kernel.inc"
+#undef ATTN_VARLEN
+#define ATTN_VARLEN 1
+#include "attn_bwd_dkdv_kernel.inc"
+#undef ATTN_VARLEN
 
 // ------------------------------------------------------------------------------------------
 // bwd_dkdv, wave-specialised variant (the role split of paper Sec. 3.2.2 -- one set of warps
@@ -641,201 +418,12 @@ attn_bwd_dkdv_ws_kernel(const bf16* __restrict__ q, const bf16* __restrict__ k, 
         }
 }
 
-// ------------------------------------------------------------------------------------------
-// bwd_dq: block = 4 waves = 128 queries (32 per wave); K/V tiles of 64 keys stream through
-// LDS (double buffered); this wave's Q and dO rows stay in registers as B operands.
-#ifndef ATTN_DQ_OCC
-#define ATTN_DQ_OCC (DQK <= 128 ? 2 : 1)
-#endif
-template <int DQK, int DV, bool CAUSAL>
-__global__ void __launch_bounds__(BWD_NT, ATTN_DQ_OCC)
-attn_bwd_dq_kernel(const bf16* __restrict__ q, const bf16* __restrict__ k, const bf16* __restrict__ v,
-                   const bf16* __restrict__ d_o, const float* __restrict__ lse2, const float* __restrict__ D,
-                   bf16* __restrict__ dq, int H, int Hkv, int N, float scale, float scale_log2e)
-{
-    constexpr int KSQ = DQK / 16, KSV = DV / 16;
-    constexpr int DBQ = DQK / 32;
-    constexpr int KB = DQ_BN / 32;
-    constexpr int K_TILE_BYTES = DQ_BN * DQK * 2;
-    constexpr int V_TILE_BYTES = DQ_BN * DV * 2;
-
-    extern __shared__ __attribute__((aligned(1024))) char smem_raw[];
-    ATTN_LDS char* smem = (ATTN_LDS char*)smem_raw;
-    ATTN_LDS char* k_lds[2] = {smem, smem + K_TILE_BYTES};
-    ATTN_LDS char* v_lds[2] = {smem + 2 * K_TILE_BYTES, smem + 2 * K_TILE_BYTES + V_TILE_BYTES};
-
-    const int tid = threadIdx.x;
-    const int wave = tid >> 6, lane = tid & 63;
-    const int c = lane & 31, h = lane >> 5;
-    const int i16 = lane & 15;
-    const int tr_row = 4 * h + (i16 >> 2);                          // keys, order 8s + 4h + j
-    const int tr_chunk = 2 * ((lane >> 4) & 1) + ((i16 & 3) >> 1);
-    const int tr_half = (i16 & 1) * 8;
-
-    const int ntq = N / DQ_BM;
-    const int total = gridDim.x;
-    int vid = blockIdx.x;
-    if ((total & 7) == 0) vid = (blockIdx.x & 7) * (total >> 3) + (blockIdx.x >> 3);
-    const int bh = vid / ntq;
-    int qt = vid - bh * ntq;
-    if (CAUSAL) qt = ntq - 1 - qt;          // longest tiles first
-    const int b = bh / H, hq = bh - b * H;
-    const int kvh = hq / (H / Hkv);
-    const int q0 = qt * DQ_BM;
-    const int qw0 = q0 + wave * 32;
-
-    const int64_t q_stride = (int64_t)H * DQK, o_stride = (int64_t)H * DV;
-    const int64_t k_stride = (int64_t)Hkv * DQK, v_stride = (int64_t)Hkv * DV;
-    const bf16* kg = k + ((int64_t)b * N * Hkv + kvh) * DQK;
-    const bf16* vg = v + ((int64_t)b * N * Hkv + kvh) * DV;
-    const int ntiles = CAUSAL ? (q0 + DQ_BM) / DQ_BN : N / DQ_BN;
-
-    TileCopy<DQ_BN, DQK, BWD_NT> kcopy;
-    TileCopy<DQ_BN, DV, BWD_NT> vcopy;
-    kcopy.init(k_stride, tid);
-    vcopy.init(v_stride, tid);
-    kcopy.issue_all(kg, k_lds[0]);
-    vcopy.issue_all(vg, v_lds[0]);
-
-    // this wave's Q and dO rows as B operands: lane = query qw0 + c, dims 16*ks + 8h .. +7
-    bf16x8 qf[KSQ], dof[KSV];
-    float lse_q, D_q;
-    {
-        const bf16* qrow = q + ((int64_t)b * N + qw0 + c) * q_stride + (int64_t)hq * DQK + 8 * h;
-        const bf16* dorow = d_o + ((int64_t)b * N + qw0 + c) * o_stride + (int64_t)hq * DV + 8 * h;
-#pragma unroll
-        for (int ks = 0; ks < KSQ; ++ks) qf[ks] = *(const bf16x8*)(qrow + 16 * ks);
-#pragma unroll
-        for (int ks = 0; ks < KSV; ++ks) dof[ks] = *(const bf16x8*)(dorow + 16 * ks);
-        lse_q = lse2[((int64_t)b * H + hq) * N + qw0 + c];
-        D_q = D[((int64_t)b * H + hq) * N + qw0 + c];
-#pragma unroll
-        for (int ks = 0; ks < KSQ; ++ks) pin_ready(qf[ks]);
-#pragma unroll
-        for (int ks = 0; ks < KSV; ++ks) pin_ready(dof[ks]);
-        pin_ready(lse_q);
-        pin_ready(D_q);
-    }
-
-    f32x16 dq_acc[DBQ];
-#pragma unroll
-    for (int db = 0; db < DBQ; ++db)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) dq_acc[db][r] = 0.f;
-
-    auto tile_step = [&](auto bufc, int j) {
-        const int buf = bufc;               // compile-time constant in the unrolled variants
-        wait_async_copies();
-        __syncthreads();
-        if (j + 1 < ntiles) {
-            kcopy.issue_all(kg + (int64_t)(j + 1) * DQ_BN * k_stride, k_lds[buf ^ 1]);
-            vcopy.issue_all(vg + (int64_t)(j + 1) * DQ_BN * v_stride, v_lds[buf ^ 1]);
-        }
-        const int key0 = j * DQ_BN;
-        if (CAUSAL && key0 > qw0 + 31) return;
-
-        // K^T fragments for the dQ contraction (transposing reads of the same K tile)
-        bf16x4 tfr[2][DBQ][2];
-        auto load_t = [&](int kk, bf16x4 (*dst)[2]) {
-            const ATTN_LDS char* base = k_lds[buf] + tr_half;
-#pragma unroll
-            for (int db = 0; db < DBQ; ++db) {
-                dst[db][0] = lds_read_tr(base + tile_off<DQK>(16 * kk + tr_row, 4 * db + tr_chunk));
-                dst[db][1] = lds_read_tr(base + tile_off<DQK>(16 * kk + 8 + tr_row, 4 * db + tr_chunk));
-            }
-        };
-
-        // ---- per block of 32 keys: S^T = K Q_w^T, dP^T = V dO_w^T, then
-        // dS^T = P^T o (dP^T - D) with P^T = 2^(c S^T - LSE2); the key index is the register row.
-        // One accumulator pair is reused for both key blocks (register budget: 2 waves per SIMD).
-        const bool diag = CAUSAL && (key0 + DQ_BN - 1 > qw0);
-        bf16x8 dsf[KB][2];
-#pragma unroll
-        for (int kb = 0; kb < KB; ++kb) {
-            f32x16 s, dp;
-#pragma unroll
-            for (int r = 0; r < 16; ++r) { s[r] = 0.f; dp[r] = 0.f; }
-#ifndef ATTN_DQ_GRP
-#define ATTN_DQ_GRP 2
-#endif
-            constexpr int GRP = ATTN_DQ_GRP, PER = KSQ + KSV, NG = PER / GRP;
-            static_assert(KSQ % GRP == 0 && KSV % GRP == 0, "k-steps must split into whole groups");
-            bf16x8 fr[2][GRP];
-            auto load_a = [&](int g, bf16x8* dst) {
-#pragma unroll
-                for (int t = 0; t < GRP; ++t) {
-                    // alternate K and V fragments so that the S and dP accumulation chains
-                    // interleave; the K-only remainder (d_qk > d_v) comes last
-                    const int st = g * GRP + t;
-                    const bool from_k = st >= 2 * KSV || (st & 1) == 0;
-                    const int u = st >= 2 * KSV ? st - KSV : st >> 1;
-                    dst[t] = from_k
-                        ? lds_read_b128(k_lds[buf] + tile_off<DQK>(32 * kb + c, 2 * u + h))
-                        : lds_read_b128(v_lds[buf] + tile_off<DV>(32 * kb + c, 2 * u + h));
-                }
-            };
-            static_assert(KSQ >= KSV, "interleave assumes d_qk >= d_v");
-            load_a(0, fr[0]);
-#pragma unroll
-            for (int g = 0; g < NG; ++g) {
-                if (g + 1 < NG) load_a(g + 1, fr[(g + 1) & 1]);
-                sched_fence();
-#pragma unroll
-                for (int t = 0; t < GRP; ++t) {
-                    const int st = g * GRP + t;
-                    const bool from_k = st >= 2 * KSV || (st & 1) == 0;
-                    const int u = st >= 2 * KSV ? st - KSV : st >> 1;
-                    if (from_k) s = mfma32(fr[g & 1][t], qf[u], s);
-                    else dp = mfma32(fr[g & 1][t], dof[u], dp);
-                }
-                sched_fence();
-            }
-            if (kb == KB - 1) { load_t(0, tfr[0]); sched_fence(); }   // in flight during the last elementwise block
-            if (diag) {   // masked scores -> -inf -> P = 0 -> dS = 0
-                const int lim = qw0 + c - key0 - 32 * kb - 4 * h;      // register row 8(r/4) + r%4 > lim is masked
-#pragma unroll
-                for (int r = 0; r < 16; ++r)
-                    if (8 * (r >> 2) + (r & 3) > lim) s[r] = -INFINITY;
-            }
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const float p = fast_exp2(fmaf(s[r], scale_log2e, -lse_q));
-                dsf[kb][r >> 3][r & 7] = (bf16)(p * (dp[r] + D_q));      // D_q holds -D
-            }
-        }
-
-        // ---- dQ_w^T += K^T dS^T : contraction over the 64 keys in 4 steps of 16
-#pragma unroll
-        for (int kk = 0; kk < 2 * KB; ++kk) {
-            if (kk + 1 < 2 * KB) load_t(kk + 1, tfr[(kk + 1) & 1]);
-            sched_fence();
-#pragma unroll
-            for (int db = 0; db < DBQ; ++db)
-                dq_acc[db] = mfma32(cat4(tfr[kk & 1][db][0], tfr[kk & 1][db][1]), dsf[kk >> 1][kk & 1], dq_acc[db]);
-            sched_fence();
-        }
-    };
-    if constexpr (DQK <= 128) {
-        for (int j = 0; j < ntiles; j += 2) {      // ntiles is even
-            tile_step(std::integral_constant<int, 0>{}, j);
-            tile_step(std::integral_constant<int, 1>{}, j + 1);
-        }
-    } else {
-        for (int j = 0; j < ntiles; ++j) tile_step(j & 1, j);
-    }
-
-    // ---- epilogue: dq = scale * dQ; the accumulator holds the transpose (dims x queries)
-    bf16* dqrow = dq + ((int64_t)b * N + qw0 + c) * q_stride + (int64_t)hq * DQK;
-#pragma unroll
-    for (int db = 0; db < DBQ; ++db)
-#pragma unroll
-        for (int r4 = 0; r4 < 4; ++r4) {
-            bf16x4 out;
-#pragma unroll
-            for (int e = 0; e < 4; ++e) out[e] = (bf16)(dq_acc[db][4 * r4 + e] * scale);
-            *(bf16x4*)(dqrow + 32 * db + 8 * r4 + 4 * h) = out;
-        }
-}
+#define ATTN_VARLEN 0
+#include "attn_bwd_dq_kernel.inc"
+#undef ATTN_VARLEN
+#define ATTN_VARLEN 1
+#include "attn_bwd_dq_kernel.inc"
+#undef ATTN_VARLEN
 
 template <typename K>
 static bool allow_big_lds(K kern, int smem, bool& done)
@@ -848,9 +436,49 @@ static bool allow_big_lds(K kern, int smem, bool& done)
     return true;
 }
 
+// Variable-length backward: the prepare kernel sees the packed batch as one sequence of T rows
+// (its outputs are then laid out [H, T]); dK/dV and dQ use the plan table.  Every head dim uses
+// the unspecialised dK/dV kernel here.
+template <int DQK, int DV, bool CAUSAL>
+static int launch_bwd_varlen_t(const BwdArgs& a)
+{
+    void* st = a.stream;
+    const int64_t nrows = (int64_t)a.T * a.H;
+    if (a.phases & 1) {
+        constexpr int RPB = 256 / (DV / 8);
+        if (launch_kernel(bwd_prepare_kernel<DV>, dim3((unsigned)((nrows + RPB - 1) / RPB)), dim3(256), 0, st,
+                          (const bf16*)a.o, (const bf16*)a.d_o, a.lse, a.D, a.lse2, a.H, a.T, nrows) != hipSuccess)
+            return -3;
+    }
+    if (a.phases & 2) {
+        constexpr int smem = 2 * BWD_BQ * (DQK + DV) * 2 + 1024;
+        auto kern = attn_bwd_dkdv_varlen_kernel<DQK, DV, CAUSAL>;
+        static bool attr_done = false;
+        if (!allow_big_lds(kern, smem, attr_done)) return -3;
+        if (launch_kernel(kern, dim3(a.max_tiles * a.Hkv), dim3(BWD_NT), smem, st,
+                          (const bf16*)a.q, (const bf16*)a.k, (const bf16*)a.v, (const bf16*)a.d_o,
+                          (const float*)a.lse2, (const float*)a.D, (bf16*)a.dk, (bf16*)a.dv,
+                          a.H, a.Hkv, a.scale, a.scale * kLog2e, (const int4*)a.plan, a.T, a.max_tiles) != hipSuccess)
+            return -3;
+    }
+    if (a.phases & 4) {
+        constexpr int smem = 2 * DQ_BN * (DQK + DV) * 2;
+        auto kern = attn_bwd_dq_varlen_kernel<DQK, DV, CAUSAL>;
+        static bool attr_done = false;
+        if (!allow_big_lds(kern, smem, attr_done)) return -3;
+        if (launch_kernel(kern, dim3(a.max_tiles * a.H), dim3(BWD_NT), smem, st,
+                          (const bf16*)a.q, (const bf16*)a.k, (const bf16*)a.v, (const bf16*)a.d_o,
+                          (const float*)a.lse2, (const float*)a.D, (bf16*)a.dq,
+                          a.H, a.Hkv, a.scale, a.scale * kLog2e, (const int4*)a.plan, a.T, a.max_tiles) != hipSuccess)
+            return -3;
+    }
+    return 0;
+}
+
 template <int DQK, int DV, bool CAUSAL>
 static int launch_bwd_t(const BwdArgs& a)
 {
+    if (a.plan) return launch_bwd_varlen_t<DQK, DV, CAUSAL>(a);
     void* st = a.stream;
     const int64_t nrows = (int64_t)a.B * a.N * a.H;
     if (a.phases & 1) {
