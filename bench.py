@@ -106,6 +106,37 @@ def write_table(path, workloads, n=10, warm=5):
         f.write("\n".join(rows) + "\n")
 
 
+def write_varlen_table(path, workloads, n=10, warm=5):
+    """The same protocol for the packed variable-length entry points; FLOPs = sum over sequences of
+    the fixed-length formula."""
+    import torch
+    import paper_2603_05451_amd as A
+    from paper_2603_05451_amd import inputs as I
+    rows = ["| workload | B | H/Hkv | lengths (min / median / max) | tokens | d_qk/d_v | causal | fwd ms | fwd TFLOP/s | % peak | bwd ms | bwd TFLOP/s | % peak |",
+            "|---|---|---|---|---|---|---|---|---|---|---|---|---|"]
+    for w in workloads:
+        x = I.make_varlen_inputs(w)
+        q, k, v, do, cu = (x[m].cuda() for m in ("q", "k", "v", "do", "cu_seqlens"))
+        T = q.shape[0]
+        o = torch.empty((T, w.H, w.dv), dtype=torch.bfloat16, device="cuda")
+        lse = torch.empty((w.H, T), dtype=torch.float32, device="cuda")
+        dq, dk, dv = torch.empty_like(q), torch.empty_like(k), torch.empty_like(v)
+        ws = torch.empty(A.attn_varlen_workspace_bytes(w.B, T, w.H, w.Hkv, w.dqk, w.dv, True), dtype=torch.uint8, device="cuda")
+        fwd = lambda: A.attn_varlen_fwd(q, k, v, cu, w.scale, w.causal, o, lse, ws)
+        bwd = lambda: A.attn_varlen_bwd(q, k, v, o, do, lse, cu, w.scale, w.causal, dq, dk, dv, ws)
+        for _ in range(warm):
+            fwd(); bwd()
+        mf, mb = event_ms(fwd, n), event_ms(bwd, n)
+        tf, tb = w.fwd_flops() / mf / 1e9, w.bwd_flops() / mb / 1e9
+        ls = sorted(w.lengths())
+        rows.append(f"| {w.name} | {w.B} | {w.H}/{w.Hkv} | {ls[0]} / {ls[len(ls) // 2]} / {ls[-1]} | {T} | {w.dqk}/{w.dv} | "
+                    f"{int(w.causal)} | {mf:.3f} | {tf:.0f} | {100 * tf / PEAK_BF16_TFLOPS:.1f} | {mb:.3f} | {tb:.0f} | "
+                    f"{100 * tb / PEAK_BF16_TFLOPS:.1f} |")
+        del q, k, v, do, o, lse, dq, dk, dv, ws
+    with open(path, "w") as f:
+        f.write("\n".join(rows) + "\n")
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -115,6 +146,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--table", metavar="FILE", default=None,
                     help="also time every workload of the task's config list and write a markdown table to FILE")
+    ap.add_argument("--varlen-table", metavar="FILE", default=None,
+                    help="time the variable-length workloads instead, write a markdown table, print nothing else")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one 1 GiB device-to-device copy (reference for rocprofv3 FETCH_SIZE/WRITE_SIZE)")
     args = ap.parse_args()
@@ -127,6 +160,10 @@ def main():
     from paper_2603_05451_amd import inputs as I
     if not torch.cuda.is_available():
         sys.exit("bench.py: no GPU visible; there is no CPU fallback for the hot path")
+
+    if args.varlen_table:
+        write_varlen_table(args.varlen_table, [I.VARLEN_MIX, I.VARLEN_MIX_GQA, I.VARLEN_MIX_D64])
+        return
 
     named = {w.name: w for w in [I.CANARY, I.TARGET, I.GQA, I.MLA_OUTLIER] + I.SWEEP_D64_NC + I.SWEEP_D128_C}
     named["target"] = I.TARGET

@@ -59,6 +59,57 @@ SWEEP_D64_NC = sweep(64, False, 2)
 SWEEP_D128_C = sweep(128, True, 3)
 
 
+@dataclass(frozen=True)
+class VarlenWorkload:
+    """A packed batch of sequences of different lengths (paper Sec. 3.3: mixed prefill batches).
+    Lengths are log-uniform integers in [lo, hi], drawn with the workload's seed and given in
+    DRAWN order (not sorted: ordering is the library's job)."""
+    name: str
+    B: int
+    H: int
+    Hkv: int
+    lo: int
+    hi: int
+    dqk: int
+    dv: int
+    causal: bool
+    seed: int
+
+    @property
+    def scale(self) -> float:
+        return 1.0 / float(self.dqk) ** 0.5
+
+    def lengths(self):
+        g = torch.Generator(device="cpu")
+        g.manual_seed(self.seed + 1000)
+        u = torch.rand(self.B, generator=g, dtype=torch.float64)
+        import math
+        return [int(round(math.exp(math.log(self.lo) + float(x) * (math.log(self.hi) - math.log(self.lo))))) for x in u]
+
+    def fwd_flops(self) -> float:
+        f = sum(2.0 * n * n * (self.dqk + self.dv) * self.H for n in self.lengths())
+        return f / 2 if self.causal else f
+
+    def bwd_flops(self) -> float:
+        return 2.5 * self.fwd_flops()
+
+
+VARLEN_MIX = VarlenWorkload("varlen_mix_B32_d128_c", 32, 16, 16, 64, 8192, 128, 128, True, 7)
+VARLEN_MIX_GQA = VarlenWorkload("varlen_mix_B32_gqa_d128_c", 32, 32, 8, 64, 8192, 128, 128, True, 8)
+VARLEN_MIX_D64 = VarlenWorkload("varlen_mix_B32_d64_nc", 32, 16, 16, 64, 8192, 64, 64, False, 9)
+
+
+def make_varlen_inputs(w: VarlenWorkload, with_do: bool = True):
+    """Packed bf16 CPU tensors q [T,H,dqk], k [T,Hkv,dqk], v [T,Hkv,dv], do [T,H,dv] (the recipe of
+    make_inputs with B = 1 and N = T) and cu_seqlens [B+1] int32."""
+    lens = w.lengths()
+    T = sum(lens)
+    x = make_inputs(Workload(w.name, 1, w.H, w.Hkv, T, w.dqk, w.dv, w.causal, w.seed), with_do=with_do)
+    out = {n: t[0] for n, t in x.items()}
+    out["cu_seqlens"] = torch.tensor([0] + list(torch.tensor(lens).cumsum(0).tolist()), dtype=torch.int32)
+    return out
+
+
 def make_inputs(w: Workload, with_do: bool = True):
     """Return bf16 CPU tensors q [B,N,H,dqk], k [B,N,Hkv,dqk], v [B,N,Hkv,dv], do [B,N,H,dv]."""
     g = torch.Generator(device="cpu")

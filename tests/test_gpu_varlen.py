@@ -127,3 +127,73 @@ def test_varlen_bwd_matches_fixed_length_and_is_reproducible():
                  max_abs=2e-2, rel_fro=5e-3)
     assert_close(r1[2].reshape(dv.shape).float().cpu().numpy(), dv.float().cpu().numpy(), "varlen dV vs fixed",
                  max_abs=2e-2, rel_fro=5e-3)
+
+
+def test_varlen_mixed_batch_sampled(oracle):
+    """The benchmark's mixed batch (32 sequences, 64 .. 8192 tokens, causal, d = 128): forward and
+    backward at full size; the oracle checks whole short sequences and, of the longest one, sampled
+    query rows (O, LSE, dQ) and the last 256 keys' dK / dV (complete under the causal mask: only
+    the last 256 query rows reach them)."""
+    import paper_2603_05451_amd as A
+    w = I.VARLEN_MIX
+    x = I.make_varlen_inputs(w)
+    lens = w.lengths()
+    cu = x["cu_seqlens"].numpy()
+    q, k, v, do, cud = (x[m].cuda() for m in ("q", "k", "v", "do", "cu_seqlens"))
+    o, lse = A.attn_varlen_fwd(q, k, v, cud, w.scale, w.causal)
+    dq, dk, dv = A.attn_varlen_bwd(q, k, v, o, do, lse, cud, w.scale, w.causal)
+    torch.cuda.synchronize()
+    o, lse, dq, dk, dv = (t.float().cpu().numpy() for t in (o, lse, dq, dk, dv))
+    assert all(np.isfinite(t).all() for t in (o, lse, dq, dk, dv))
+    hs = slice(0, 2)                                            # two of the 16 heads (Hkv = H here)
+    order = np.argsort(lens)
+    for b in list(order[:3]) + [order[len(order) // 2]]:        # three shortest and the median sequence, whole
+        s = slice(int(cu[b]), int(cu[b + 1]))
+        f = lambda m: I.to_f64(x[m][s][None, :, hs])
+        ro, rlse = oracle.attn_fwd(f("q"), f("k"), f("v"), w.scale, w.causal)
+        rdq, rdk, rdv = oracle.attn_bwd(f("q"), f("k"), f("v"), f("do"), w.scale, w.causal)
+        assert_close(o[s][None, :, hs], ro, f"varlen mix O seq{b} len{lens[b]}")
+        assert np.abs(lse[hs, s][None] - rlse).max() <= LSE_ABS
+        assert_close(dq[s][None, :, hs], rdq, f"varlen mix dQ seq{b}")
+        assert_close(dk[s][None, :, hs], rdk, f"varlen mix dK seq{b}")
+        assert_close(dv[s][None, :, hs], rdv, f"varlen mix dV seq{b}")
+    b = int(order[-1])                                          # the longest sequence
+    n = lens[b]
+    s = slice(int(cu[b]), int(cu[b + 1]))
+    rng = np.random.default_rng(5)
+    rows = np.unique(np.concatenate([[0, 1, 63, 64, 127, 128, n - 2, n - 1], rng.integers(0, n, 40),
+                                     np.arange(n - 256, n)]))
+    f = lambda m: I.to_f64(x[m][s][None, :, hs])
+    ro, rlse = oracle.attn_fwd(f("q")[:, rows], f("k"), f("v"), w.scale, w.causal, q_pos=rows)
+    rdq, rdk, rdv = oracle.attn_bwd(f("q")[:, rows], f("k"), f("v"), f("do")[:, rows], w.scale, w.causal, q_pos=rows)
+    assert_close(o[s][None, :, hs][:, rows], ro, f"varlen mix O longest len{n}")
+    assert np.abs(lse[hs, s][None][:, :, rows] - rlse).max() <= LSE_ABS
+    assert_close(dq[s][None, :, hs][:, rows], rdq, "varlen mix dQ longest")
+    assert_close(dk[s][None, n - 256:, hs], rdk[:, n - 256:], "varlen mix dK longest, last 256 keys")
+    assert_close(dv[s][None, n - 256:, hs], rdv[:, n - 256:], "varlen mix dV longest, last 256 keys")
+
+
+def test_varlen_many_short_sequences(oracle):
+    """1500 sequences of 1 .. 40 tokens: more sequences than plan-kernel threads, every tile ragged."""
+    import paper_2603_05451_amd as A
+    rng = np.random.default_rng(11)
+    lengths = [int(n) for n in rng.integers(1, 41, 1500)]
+    x, cu, scale = packed_inputs(lengths, 2, 1, 64, 64, 51, with_do=True)
+    q, k, v, do = (x[m].cuda() for m in ("q", "k", "v", "do"))
+    cud = torch.from_numpy(cu).cuda()
+    o, lse = A.attn_varlen_fwd(q, k, v, cud, scale, True)
+    dq, dk, dv = A.attn_varlen_bwd(q, k, v, o, do, lse, cud, scale, True)
+    torch.cuda.synchronize()
+    o, dq, dk, dv = (t.float().cpu().numpy() for t in (o, dq, dk, dv))
+    assert all(np.isfinite(t).all() for t in (o, dq, dk, dv))
+    for b in list(range(0, 1500, 97)) + [1499]:
+        s = slice(int(cu[b]), int(cu[b + 1]))
+        f = lambda m: I.to_f64(x[m][s][None])
+        ro, _ = oracle.attn_fwd(f("q"), f("k"), f("v"), scale, True)
+        rdq, rdk, rdv = oracle.attn_bwd(f("q"), f("k"), f("v"), f("do"), scale, True)
+        # short sequences give peaked softmaxes and gradients of magnitude 4 .. 8, where one bf16
+        # half-ulp of the OUTPUT is 1.6e-2 already: absolute bound plus the output-rounding term
+        # (parity.assert_close_wide's bound, without the Frobenius part: sequences this short have
+        # exactly-zero reference rows)
+        ok = lambda got, ref: (np.abs(got - ref) <= 2e-2 + 2.0 ** -8 * np.abs(ref)).all()
+        assert ok(o[s][None], ro) and ok(dq[s][None], rdq) and ok(dk[s][None], rdk) and ok(dv[s][None], rdv)
