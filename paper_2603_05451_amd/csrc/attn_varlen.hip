@@ -20,20 +20,33 @@ constexpr int PLAN_BUCKETS = 4096;      // tile counts 0 .. 4095 (sequences up t
 __global__ void __launch_bounds__(PLAN_NT)
 varlen_plan_kernel(const int* __restrict__ cu, int B, int4* __restrict__ plan, int max_tiles)
 {
+    static_assert(PLAN_BUCKETS == 4 * PLAN_NT, "four buckets per thread in the scan below");
     __shared__ int hist[PLAN_BUCKETS];       // sequences per tile count, then next free slot per bucket
     __shared__ int tile_start[PLAN_BUCKETS]; // first plan entry of each bucket
+    __shared__ int part[PLAN_NT];
     const int tid = threadIdx.x;
     for (int i = tid; i < PLAN_BUCKETS; i += PLAN_NT) hist[i] = 0;
     for (int i = tid; i < max_tiles; i += PLAN_NT) plan[i] = make_int4(0, 0, 0, 0);
     __syncthreads();
+#ifdef ATTN_PLAN_GIVEN_ORDER   // measurement only: the batch order as given, no sort
+    if (tid == 0) {
+        int run = 0;
+        for (int b = 0; b < B; ++b) {
+            const int len = cu[b + 1] - cu[b], nt = (len + 127) / 128;
+            for (int t = 0; t < nt && run < max_tiles; ++t) plan[run++] = make_int4(cu[b], len, nt - 1 - t, 1);
+        }
+    }
+    return;
+#endif
     auto bucket_of = [](int nt) { return nt < PLAN_BUCKETS ? nt : PLAN_BUCKETS - 1; };
     for (int b = tid; b < B; b += PLAN_NT) {
         const int len = cu[b + 1] - cu[b];
         if (len > 0) atomicAdd(&hist[bucket_of((len + 127) / 128)], 1);
     }
     __syncthreads();
-    // Exclusive scan over the buckets from the largest tile count down.  Sequences in the top
-    // bucket may differ in tile count, so that bucket is laid out by one thread sequentially.
+    // Sequences in the top bucket may differ in tile count, so that (normally empty) bucket is
+    // laid out first, by one thread, sequentially.
+    __shared__ int top_tiles;
     if (tid == 0) {
         int run = 0;
         if (hist[PLAN_BUCKETS - 1] > 0) {
@@ -44,12 +57,32 @@ varlen_plan_kernel(const int* __restrict__ cu, int B, int4* __restrict__ plan, i
                     for (int t = 0; t < nt && run < max_tiles; ++t) plan[run++] = make_int4(cu[b], len, nt - 1 - t, 1);
             }
         }
-        for (int nt = PLAN_BUCKETS - 2; nt >= 1; --nt) {
-            tile_start[nt] = run;
-            run += hist[nt] * nt;
-            hist[nt] = 0;                    // becomes the per-bucket sequence counter
-        }
+        top_tiles = run;
     }
+    // Exclusive prefix sum of hist[nt] * nt over the other buckets from the largest tile count
+    // down.  Position p = 0 .. PLAN_BUCKETS-1 stands for bucket PLAN_BUCKETS-2-p (p beyond that: empty);
+    // every thread owns four consecutive positions.
+    auto weight = [&](int p) { const int nt = PLAN_BUCKETS - 2 - p; return nt >= 1 ? hist[nt] * nt : 0; };
+    int w[4], local = 0;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) { w[e] = weight(4 * tid + e); local += w[e]; }
+    part[tid] = local;
+    __syncthreads();
+    for (int off = 1; off < PLAN_NT; off <<= 1) {          // inclusive Hillis-Steele scan of the partials
+        const int add = tid >= off ? part[tid - off] : 0;
+        __syncthreads();
+        part[tid] += add;
+        __syncthreads();
+    }
+    int run = top_tiles + part[tid] - local;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        const int nt = PLAN_BUCKETS - 2 - (4 * tid + e);
+        if (nt >= 1) tile_start[nt] = run;
+        run += w[e];
+    }
+    __syncthreads();
+    for (int i = tid; i < PLAN_BUCKETS - 1; i += PLAN_NT) hist[i] = 0;   // becomes the per-bucket sequence counter
     __syncthreads();
     for (int b = tid; b < B; b += PLAN_NT) {
         const int start = cu[b], len = cu[b + 1] - start;
