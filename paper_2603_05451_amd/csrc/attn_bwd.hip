@@ -115,17 +115,6 @@ constexpr int WS_PDS_BYTES = 4 * 8 * 1024;   // 4 key groups x (2 query blocks x
 #include "attn_bwd_dq_kernel.inc"
 #undef ATTN_VARLEN
 
-template <typename K>
-static bool allow_big_lds(K kern, int smem, bool& done)
-{
-    if (!done) {   // idempotent; a race only repeats the call
-        if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, smem) != hipSuccess)
-            return false;
-        done = true;
-    }
-    return true;
-}
-
 // Variable-length backward: the prepare kernel sees the packed batch as one sequence of T rows
 // (its outputs are then laid out [H, T]); dK/dV and dQ use the plan table.
 template <int DQK, int DV, bool CAUSAL>
@@ -142,8 +131,8 @@ static int launch_bwd_varlen_t(const BwdArgs& a)
     if constexpr (DQK == 128) { if (a.phases & 2) {
         constexpr int smem = WS_STAGES * (BWD_BQ * (DQK + DV) * 2 + 512) + WS_PDS_BYTES;
         auto kern = attn_bwd_dkdv_ws_varlen_kernel<DQK, DV, CAUSAL>;
-        static bool attr_done = false;
-        if (!allow_big_lds(kern, smem, attr_done)) return -3;
+        static LdsOptIn lds;
+        if (!lds.allow(kern, smem)) return -3;
         if (launch_kernel(kern, dim3(a.max_tiles * a.Hkv), dim3(WS_NT), smem, st,
                           (const bf16*)a.q, (const bf16*)a.k, (const bf16*)a.v, (const bf16*)a.d_o,
                           (const float*)a.lse2, (const float*)a.D, (bf16*)a.dk, (bf16*)a.dv,
@@ -152,8 +141,8 @@ static int launch_bwd_varlen_t(const BwdArgs& a)
     } } else if (a.phases & 2) {
         constexpr int smem = 2 * BWD_BQ * (DQK + DV) * 2 + 1024;
         auto kern = attn_bwd_dkdv_varlen_kernel<DQK, DV, CAUSAL>;
-        static bool attr_done = false;
-        if (!allow_big_lds(kern, smem, attr_done)) return -3;
+        static LdsOptIn lds;
+        if (!lds.allow(kern, smem)) return -3;
         if (launch_kernel(kern, dim3(a.max_tiles * a.Hkv), dim3(BWD_NT), smem, st,
                           (const bf16*)a.q, (const bf16*)a.k, (const bf16*)a.v, (const bf16*)a.d_o,
                           (const float*)a.lse2, (const float*)a.D, (bf16*)a.dk, (bf16*)a.dv,
@@ -163,8 +152,8 @@ static int launch_bwd_varlen_t(const BwdArgs& a)
     if (a.phases & 4) {
         constexpr int smem = 2 * DQ_BN * (DQK + DV) * 2;
         auto kern = attn_bwd_dq_varlen_kernel<DQK, DV, CAUSAL>;
-        static bool attr_done = false;
-        if (!allow_big_lds(kern, smem, attr_done)) return -3;
+        static LdsOptIn lds;
+        if (!lds.allow(kern, smem)) return -3;
         if (launch_kernel(kern, dim3(a.max_tiles * a.H), dim3(BWD_NT), smem, st,
                           (const bf16*)a.q, (const bf16*)a.k, (const bf16*)a.v, (const bf16*)a.d_o,
                           (const float*)a.lse2, (const float*)a.D, (bf16*)a.dq,
@@ -192,8 +181,8 @@ static int launch_bwd_t(const BwdArgs& a)
     if constexpr (ATTN_DKDV_WS && DQK == 128) { if (a.phases & 2) {
         constexpr int smem = WS_STAGES * (BWD_BQ * (DQK + DV) * 2 + 512) + WS_PDS_BYTES;
         auto kern = attn_bwd_dkdv_ws_kernel<DQK, DV, CAUSAL>;
-        static bool attr_done = false;
-        if (!allow_big_lds(kern, smem, attr_done)) return -3;
+        static LdsOptIn lds;
+        if (!lds.allow(kern, smem)) return -3;
         const int grid = a.B * a.Hkv * (a.N / BWD_BK);
         if (launch_kernel(kern, dim3(grid), dim3(WS_NT), smem, st,
                           (const bf16*)a.q, (const bf16*)a.k, (const bf16*)a.v, (const bf16*)a.d_o,
@@ -203,8 +192,8 @@ static int launch_bwd_t(const BwdArgs& a)
     } } else if (a.phases & 2) {
         constexpr int smem = 2 * BWD_BQ * (DQK + DV) * 2 + 1024;
         auto kern = attn_bwd_dkdv_kernel<DQK, DV, CAUSAL>;
-        static bool attr_done = false;
-        if (!allow_big_lds(kern, smem, attr_done)) return -3;
+        static LdsOptIn lds;
+        if (!lds.allow(kern, smem)) return -3;
         const int grid = a.B * a.Hkv * (a.N / BWD_BK);
         if (launch_kernel(kern, dim3(grid), dim3(BWD_NT), smem, st,
                           (const bf16*)a.q, (const bf16*)a.k, (const bf16*)a.v, (const bf16*)a.d_o,
@@ -215,8 +204,8 @@ static int launch_bwd_t(const BwdArgs& a)
     if (a.phases & 4) {
         constexpr int smem = 2 * DQ_BN * (DQK + DV) * 2;
         auto kern = attn_bwd_dq_kernel<DQK, DV, CAUSAL>;
-        static bool attr_done = false;
-        if (!allow_big_lds(kern, smem, attr_done)) return -3;
+        static LdsOptIn lds;
+        if (!lds.allow(kern, smem)) return -3;
         const int grid = a.B * a.H * (a.N / DQ_BM);
         if (launch_kernel(kern, dim3(grid), dim3(BWD_NT), smem, st,
                           (const bf16*)a.q, (const bf16*)a.k, (const bf16*)a.v, (const bf16*)a.d_o,

@@ -38,17 +38,6 @@ constexpr int FWD_NT = 256;
 #include "attn_fwd_kernel.inc"
 #undef ATTN_VARLEN
 
-template <typename K>
-static bool allow_lds(K kern, int smem, bool& done)
-{
-    if (!done) {   // idempotent; a race only repeats the call
-        if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, smem) != hipSuccess)
-            return false;
-        done = true;
-    }
-    return true;
-}
-
 template <int DQK, int DV, bool CAUSAL>
 static int launch_fwd_t(const FwdArgs& a)
 {
@@ -56,15 +45,15 @@ static int launch_fwd_t(const FwdArgs& a)
     hipError_t e;
     if (a.plan) {
         auto kern = attn_fwd_varlen_kernel<DQK, DV, CAUSAL>;
-        static bool attr_done = false;
-        if (!allow_lds(kern, smem, attr_done)) return -3;
+        static LdsOptIn lds;
+        if (!lds.allow(kern, smem)) return -3;
         e = launch_kernel(kern, dim3(a.max_tiles * a.H), dim3(FWD_NT), smem, a.stream,
                           (const bf16*)a.q, (const bf16*)a.k, (const bf16*)a.v, (bf16*)a.o, a.lse,
                           a.H, a.Hkv, a.scale * kLog2e, (const int4*)a.plan, a.T, a.max_tiles);
     } else {
         auto kern = attn_fwd_kernel<DQK, DV, CAUSAL>;
-        static bool attr_done = false;
-        if (!allow_lds(kern, smem, attr_done)) return -3;
+        static LdsOptIn lds;
+        if (!lds.allow(kern, smem)) return -3;
         e = launch_kernel(kern, dim3(a.B * a.H * (a.N / FWD_BM)), dim3(FWD_NT), smem, a.stream,
                           (const bf16*)a.q, (const bf16*)a.k, (const bf16*)a.v, (bf16*)a.o, a.lse,
                           a.H, a.Hkv, a.N, a.scale * kLog2e);

@@ -49,6 +49,24 @@ inline hipError_t launch_kernel(void (*kern)(KArgs...), dim3 grid, dim3 block, s
     return hipLaunchKernel((const void*)kern, grid, block, ptrs, smem, (hipStream_t)stream);
 }
 
+// Raises a kernel's dynamic-LDS limit to `smem` bytes on the current device.  The attribute
+// belongs to the (kernel, device) pair, so the "already done" note is kept per device; a race
+// between two host threads only repeats the idempotent call.
+struct LdsOptIn {
+    bool done[64] = {};
+    template <typename K>
+    bool allow(K kern, int smem)
+    {
+        int dev = 0;
+        if (hipGetDevice(&dev) != hipSuccess) return false;
+        if (dev >= 0 && dev < 64 && done[dev]) return true;
+        if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, smem) != hipSuccess)
+            return false;
+        if (dev >= 0 && dev < 64) done[dev] = true;
+        return true;
+    }
+};
+
 // 0 on success, -2 unsupported head dims, -3 launch failure.
 int launch_fwd(const FwdArgs& a);
 int launch_bwd(const BwdArgs& a);
