@@ -128,6 +128,27 @@ int attn_varlen_bwd(const void* q, const void* k, const void* v, const void* o, 
                     const int* cu_seqlens, int B, int total_tokens, int H, int Hkv, int d_qk, int d_v,
                     float scale, int causal, void* workspace, size_t workspace_bytes, void* stream);
 
+/* The same four operations on IEEE fp16 storage (the paper's benchmarks cover FP16 and BF16
+ * inputs, Sec. 5): dtype = ATTN_BF16 is exactly the entry point without the suffix, dtype =
+ * ATTN_F16 reads q, k, v, o, d_o and writes o, dq, dk, dv as fp16 (round to nearest even), with
+ * fp16 MFMA operands (P and dS are rounded to fp16) and fp32 accumulation, statistics and LSE.
+ * Any other dtype: ATTN_EUNSUPPORTED.  All remaining arguments and conventions as in
+ * attn_fwd_ex, attn_bwd_ex, attn_varlen_fwd, attn_varlen_bwd. */
+enum { ATTN_BF16 = 0, ATTN_F16 = 1 };
+int attn_fwd_dtype(int dtype, const void* q, const void* k, const void* v, void* o, float* lse,
+                   int B, int H, int Hkv, int N, int d_qk, int d_v, float scale, int causal, void* stream);
+int attn_bwd_dtype(int dtype, const void* q, const void* k, const void* v, const void* o, const void* d_o,
+                   const float* lse, void* dq, void* dk, void* dv,
+                   int B, int H, int Hkv, int N, int d_qk, int d_v, float scale, int causal,
+                   void* workspace, size_t workspace_bytes, void* stream);
+int attn_varlen_fwd_dtype(int dtype, const void* q, const void* k, const void* v, void* o, float* lse,
+                          const int* cu_seqlens, int B, int total_tokens, int H, int Hkv, int d_qk, int d_v,
+                          float scale, int causal, void* workspace, size_t workspace_bytes, void* stream);
+int attn_varlen_bwd_dtype(int dtype, const void* q, const void* k, const void* v, const void* o, const void* d_o,
+                          const float* lse, void* dq, void* dk, void* dv,
+                          const int* cu_seqlens, int B, int total_tokens, int H, int Hkv, int d_qk, int d_v,
+                          float scale, int causal, void* workspace, size_t workspace_bytes, void* stream);
+
 /* Software 2^x of paper Sec. 3.1.3 (range reduction + degree-n minimax polynomial, p0 = 1, Horner
  * with FMAs, exponent splice), provided to measure it on this hardware; attn_fwd does not use
  * it (v_exp_f32 and the FMAs share one issue port on CDNA4, so emulation cannot add throughput).

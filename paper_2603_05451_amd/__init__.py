@@ -47,6 +47,14 @@ def lib():
         L.attn_bwd_phases.restype = i
         L.attn_bwd_workspace_bytes.argtypes = [i] * 6
         L.attn_bwd_workspace_bytes.restype = sz
+        L.attn_fwd_dtype.argtypes = [i, vp, vp, vp, vp, vp, i, i, i, i, i, i, f, i, vp]
+        L.attn_fwd_dtype.restype = i
+        L.attn_bwd_dtype.argtypes = [i] + [vp] * 9 + [i, i, i, i, i, i, f, i, vp, sz, vp]
+        L.attn_bwd_dtype.restype = i
+        L.attn_varlen_fwd_dtype.argtypes = [i] + [vp] * 6 + [i, i, i, i, i, i, f, i, vp, sz, vp]
+        L.attn_varlen_fwd_dtype.restype = i
+        L.attn_varlen_bwd_dtype.argtypes = [i] + [vp] * 10 + [i, i, i, i, i, i, f, i, vp, sz, vp]
+        L.attn_varlen_bwd_dtype.restype = i
         L.attn_varlen_workspace_bytes.argtypes = [i] * 7
         L.attn_varlen_workspace_bytes.restype = sz
         L.attn_varlen_fwd.argtypes = [vp] * 6 + [i, i, i, i, i, i, f, i, vp, sz, vp]
@@ -85,10 +93,25 @@ def _stream(stream):
     return ctypes.c_void_p(s.cuda_stream)
 
 
-def _dev_bf16(t, name, shape=None):
+ATTN_BF16, ATTN_F16 = 0, 1
+
+
+def _dtype_code(t):
+    """ATTN_BF16 / ATTN_F16 for a tensor's element type."""
     import torch
-    if not (t.is_cuda and t.dtype == torch.bfloat16 and t.is_contiguous()):
-        raise ValueError(f"{name} must be a contiguous bf16 CUDA tensor")
+    if t.dtype == torch.bfloat16:
+        return ATTN_BF16
+    if t.dtype == torch.float16:
+        return ATTN_F16
+    raise ValueError(f"unsupported element type {t.dtype}: bf16 or fp16")
+
+
+def _dev_bf16(t, name, shape=None, like=None):
+    """Device pointer of a contiguous 16-bit CUDA tensor (bf16, or the element type of `like`)."""
+    import torch
+    want = torch.bfloat16 if like is None else like.dtype
+    if not (t.is_cuda and t.dtype == want and t.is_contiguous()):
+        raise ValueError(f"{name} must be a contiguous {want} CUDA tensor")
     if shape is not None and tuple(t.shape) != tuple(shape):
         raise ValueError(f"{name} has shape {tuple(t.shape)}, expected {tuple(shape)}")
     return ctypes.c_void_p(t.data_ptr())
@@ -99,22 +122,25 @@ def attn_bwd_workspace_bytes(B, H, Hkv, N, d_qk, d_v) -> int:
 
 
 def attn_fwd(q, k, v, scale, causal, o=None, lse=None, stream=None):
-    """q [B,N,H,d_qk], k [B,N,Hkv,d_qk], v [B,N,Hkv,d_v] bf16 on the GPU -> (o [B,N,H,d_v] bf16,
-    lse [B,H,N] fp32).  Outputs are allocated with torch unless passed in."""
+    """q [B,N,H,d_qk], k [B,N,Hkv,d_qk], v [B,N,Hkv,d_v] bf16 (or all fp16) on the GPU ->
+    (o [B,N,H,d_v] of the same type, lse [B,H,N] fp32).  Outputs are allocated with torch unless
+    passed in."""
     import torch
     B, N, H, dqk = q.shape
     Hkv, dv = k.shape[2], v.shape[3]
+    code = _dtype_code(q)
     if o is None:
-        o = torch.empty((B, N, H, dv), dtype=torch.bfloat16, device=q.device)
+        o = torch.empty((B, N, H, dv), dtype=q.dtype, device=q.device)
     if lse is None:
         lse = torch.empty((B, H, N), dtype=torch.float32, device=q.device)
     if not (lse.is_cuda and lse.dtype == torch.float32 and lse.is_contiguous() and
             tuple(lse.shape) == (B, H, N)):
         raise ValueError("lse must be a contiguous fp32 CUDA tensor [B,H,N]")
-    rc = lib().attn_fwd_ex(_dev_bf16(q, "q"), _dev_bf16(k, "k", (B, N, Hkv, dqk)),
-                           _dev_bf16(v, "v", (B, N, Hkv, dv)), _dev_bf16(o, "o", (B, N, H, dv)),
-                           ctypes.c_void_p(lse.data_ptr()), B, H, Hkv, N, dqk, dv,
-                           float(scale), int(bool(causal)), _stream(stream))
+    args = (_dev_bf16(q, "q", like=q), _dev_bf16(k, "k", (B, N, Hkv, dqk), q),
+            _dev_bf16(v, "v", (B, N, Hkv, dv), q), _dev_bf16(o, "o", (B, N, H, dv), q),
+            ctypes.c_void_p(lse.data_ptr()), B, H, Hkv, N, dqk, dv,
+            float(scale), int(bool(causal)), _stream(stream))
+    rc = lib().attn_fwd_ex(*args) if code == ATTN_BF16 else lib().attn_fwd_dtype(code, *args)
     _check(rc)
     return o, lse
 
@@ -138,7 +164,7 @@ def attn_varlen_fwd(q, k, v, cu_seqlens, scale, causal, o=None, lse=None, worksp
     Hkv, dv = k.shape[1], v.shape[2]
     B = cu_seqlens.numel() - 1
     if o is None:
-        o = torch.empty((T, H, dv), dtype=torch.bfloat16, device=q.device)
+        o = torch.empty((T, H, dv), dtype=q.dtype, device=q.device)
     if lse is None:
         lse = torch.empty((H, T), dtype=torch.float32, device=q.device)
     if not (lse.is_cuda and lse.dtype == torch.float32 and lse.is_contiguous() and tuple(lse.shape) == (H, T)):
@@ -146,10 +172,12 @@ def attn_varlen_fwd(q, k, v, cu_seqlens, scale, causal, o=None, lse=None, worksp
     need = attn_varlen_workspace_bytes(B, T, H, Hkv, dqk, dv, False)
     if workspace is None:
         workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=q.device)
-    rc = lib().attn_varlen_fwd(_dev_bf16(q, "q"), _dev_bf16(k, "k", (T, Hkv, dqk)), _dev_bf16(v, "v", (T, Hkv, dv)),
-                               _dev_bf16(o, "o", (T, H, dv)), ctypes.c_void_p(lse.data_ptr()), _dev_cu(cu_seqlens, B),
-                               B, T, H, Hkv, dqk, dv, float(scale), int(bool(causal)),
-                               ctypes.c_void_p(workspace.data_ptr()), workspace.numel(), _stream(stream))
+    code = _dtype_code(q)
+    args = (_dev_bf16(q, "q", like=q), _dev_bf16(k, "k", (T, Hkv, dqk), q), _dev_bf16(v, "v", (T, Hkv, dv), q),
+            _dev_bf16(o, "o", (T, H, dv), q), ctypes.c_void_p(lse.data_ptr()), _dev_cu(cu_seqlens, B),
+            B, T, H, Hkv, dqk, dv, float(scale), int(bool(causal)),
+            ctypes.c_void_p(workspace.data_ptr()), workspace.numel(), _stream(stream))
+    rc = lib().attn_varlen_fwd(*args) if code == ATTN_BF16 else lib().attn_varlen_fwd_dtype(code, *args)
     _check(rc)
     return o, lse
 
@@ -169,12 +197,14 @@ def attn_varlen_bwd(q, k, v, o, d_o, lse, cu_seqlens, scale, causal, dq=None, dk
         workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=q.device)
     if not (lse.is_cuda and lse.dtype == torch.float32 and lse.is_contiguous() and tuple(lse.shape) == (H, T)):
         raise ValueError("lse must be a contiguous fp32 CUDA tensor [H,T]")
-    rc = lib().attn_varlen_bwd(_dev_bf16(q, "q"), _dev_bf16(k, "k", (T, Hkv, dqk)), _dev_bf16(v, "v", (T, Hkv, dv_)),
-                               _dev_bf16(o, "o", (T, H, dv_)), _dev_bf16(d_o, "d_o", (T, H, dv_)),
-                               ctypes.c_void_p(lse.data_ptr()), _dev_bf16(dq, "dq", (T, H, dqk)),
-                               _dev_bf16(dk, "dk", (T, Hkv, dqk)), _dev_bf16(dv, "dv", (T, Hkv, dv_)),
-                               _dev_cu(cu_seqlens, B), B, T, H, Hkv, dqk, dv_, float(scale), int(bool(causal)),
-                               ctypes.c_void_p(workspace.data_ptr()), workspace.numel(), _stream(stream))
+    code = _dtype_code(q)
+    args = (_dev_bf16(q, "q", like=q), _dev_bf16(k, "k", (T, Hkv, dqk), q), _dev_bf16(v, "v", (T, Hkv, dv_), q),
+            _dev_bf16(o, "o", (T, H, dv_), q), _dev_bf16(d_o, "d_o", (T, H, dv_), q),
+            ctypes.c_void_p(lse.data_ptr()), _dev_bf16(dq, "dq", (T, H, dqk), q),
+            _dev_bf16(dk, "dk", (T, Hkv, dqk), q), _dev_bf16(dv, "dv", (T, Hkv, dv_), q),
+            _dev_cu(cu_seqlens, B), B, T, H, Hkv, dqk, dv_, float(scale), int(bool(causal)),
+            ctypes.c_void_p(workspace.data_ptr()), workspace.numel(), _stream(stream))
+    rc = lib().attn_varlen_bwd(*args) if code == ATTN_BF16 else lib().attn_varlen_bwd_dtype(code, *args)
     _check(rc)
     return dq, dk, dv
 
@@ -238,13 +268,19 @@ def attn_bwd(q, k, v, o, do, lse, scale, causal, dq=None, dk=None, dv=None, work
                or ATTN_EINVAL)
     if workspace is None:
         workspace = torch.empty(need, dtype=torch.uint8, device=q.device)
-    rc = lib().attn_bwd_phases(_dev_bf16(q, "q"), _dev_bf16(k, "k", (B, N, Hkv, dqk)),
-                               _dev_bf16(v, "v", (B, N, Hkv, dvd)), _dev_bf16(o, "o", (B, N, H, dvd)),
-                               _dev_bf16(do, "do", (B, N, H, dvd)), ctypes.c_void_p(lse.data_ptr()),
-                               _dev_bf16(dq, "dq", q.shape), _dev_bf16(dk, "dk", k.shape),
-                               _dev_bf16(dv, "dv", v.shape), B, H, Hkv, N, dqk, dvd, float(scale),
-                               int(bool(causal)), ctypes.c_void_p(workspace.data_ptr()),
-                               workspace.numel() * workspace.element_size(), _stream(stream),
-                               int(phases))
+    code = _dtype_code(q)
+    args = (_dev_bf16(q, "q", like=q), _dev_bf16(k, "k", (B, N, Hkv, dqk), q),
+            _dev_bf16(v, "v", (B, N, Hkv, dvd), q), _dev_bf16(o, "o", (B, N, H, dvd), q),
+            _dev_bf16(do, "do", (B, N, H, dvd), q), ctypes.c_void_p(lse.data_ptr()),
+            _dev_bf16(dq, "dq", q.shape, q), _dev_bf16(dk, "dk", k.shape, q),
+            _dev_bf16(dv, "dv", v.shape, q), B, H, Hkv, N, dqk, dvd, float(scale),
+            int(bool(causal)), ctypes.c_void_p(workspace.data_ptr()),
+            workspace.numel() * workspace.element_size(), _stream(stream))
+    if code == ATTN_BF16:
+        rc = lib().attn_bwd_phases(*args, int(phases))
+    elif phases == ATTN_BWD_ALL:
+        rc = lib().attn_bwd_dtype(code, *args)
+    else:
+        raise ValueError("per-kernel phases are exposed for bf16 only")
     _check(rc)
     return dq, dk, dv

@@ -47,10 +47,11 @@ WorkspaceLayout workspace_layout(int B, int H, int N)
 
 extern "C" {
 
-int attn_fwd_ex(const void* q, const void* k, const void* v, void* o, float* lse,
-                int B, int H, int Hkv, int N, int d_qk, int d_v, float scale, int causal,
-                void* stream)
+int attn_fwd_dtype(int dtype, const void* q, const void* k, const void* v, void* o, float* lse,
+                   int B, int H, int Hkv, int N, int d_qk, int d_v, float scale, int causal,
+                   void* stream)
 {
+    if (dtype != ATTN_BF16 && dtype != ATTN_F16) return ATTN_EUNSUPPORTED;
     if (!q || !k || !v || !o || !lse) return ATTN_EINVAL;
     if (int rc = check_sizes(B, H, Hkv, N, d_qk, d_v)) return rc;
     if (!(scale > 0.0f) || !(scale < 1e30f)) return ATTN_EINVAL;
@@ -58,8 +59,16 @@ int attn_fwd_ex(const void* q, const void* k, const void* v, void* o, float* lse
         misaligned(lse, 4))
         return ATTN_EINVAL;
     attn::FwdArgs a{q, k, v, o, lse, B, H, Hkv, N, d_qk, d_v, scale, causal != 0, stream};
+    a.f16 = dtype == ATTN_F16;
     const int rc = attn::launch_fwd(a);
     return rc == 0 ? ATTN_OK : (rc == -2 ? ATTN_EUNSUPPORTED : ATTN_ELAUNCH);
+}
+
+int attn_fwd_ex(const void* q, const void* k, const void* v, void* o, float* lse,
+                int B, int H, int Hkv, int N, int d_qk, int d_v, float scale, int causal,
+                void* stream)
+{
+    return attn_fwd_dtype(ATTN_BF16, q, k, v, o, lse, B, H, Hkv, N, d_qk, d_v, scale, causal, stream);
 }
 
 int attn_fwd(const void* q, const void* k, const void* v, void* o, float* lse,
@@ -74,11 +83,12 @@ size_t attn_bwd_workspace_bytes(int B, int H, int Hkv, int N, int d_qk, int d_v)
     return workspace_layout(B, H, N).total;
 }
 
-int attn_bwd_phases(const void* q, const void* k, const void* v, const void* o, const void* d_o,
+static int bwd_impl(int dtype, const void* q, const void* k, const void* v, const void* o, const void* d_o,
                     const float* lse, void* dq, void* dk, void* dv,
                     int B, int H, int Hkv, int N, int d_qk, int d_v, float scale, int causal,
                     void* workspace, size_t workspace_bytes, void* stream, int phases)
 {
+    if (dtype != ATTN_BF16 && dtype != ATTN_F16) return ATTN_EUNSUPPORTED;
     if (phases <= 0 || phases > ATTN_BWD_ALL) return ATTN_EINVAL;
     if (!q || !k || !v || !o || !d_o || !lse || !dq || !dk || !dv || !workspace) return ATTN_EINVAL;
     if (int rc = check_sizes(B, H, Hkv, N, d_qk, d_v)) return rc;
@@ -93,8 +103,27 @@ int attn_bwd_phases(const void* q, const void* k, const void* v, const void* o, 
     attn::BwdArgs a{q, k, v, o, d_o, lse, dq, dk, dv, B, H, Hkv, N, d_qk, d_v, scale, causal != 0,
                     reinterpret_cast<float*>(ws + w.d_off),
                     reinterpret_cast<float*>(ws + w.lse2_off), stream, phases};
+    a.f16 = dtype == ATTN_F16;
     const int rc = attn::launch_bwd(a);
     return rc == 0 ? ATTN_OK : (rc == -2 ? ATTN_EUNSUPPORTED : ATTN_ELAUNCH);
+}
+
+int attn_bwd_phases(const void* q, const void* k, const void* v, const void* o, const void* d_o,
+                    const float* lse, void* dq, void* dk, void* dv,
+                    int B, int H, int Hkv, int N, int d_qk, int d_v, float scale, int causal,
+                    void* workspace, size_t workspace_bytes, void* stream, int phases)
+{
+    return bwd_impl(ATTN_BF16, q, k, v, o, d_o, lse, dq, dk, dv, B, H, Hkv, N, d_qk, d_v, scale, causal,
+                    workspace, workspace_bytes, stream, phases);
+}
+
+int attn_bwd_dtype(int dtype, const void* q, const void* k, const void* v, const void* o, const void* d_o,
+                   const float* lse, void* dq, void* dk, void* dv,
+                   int B, int H, int Hkv, int N, int d_qk, int d_v, float scale, int causal,
+                   void* workspace, size_t workspace_bytes, void* stream)
+{
+    return bwd_impl(dtype, q, k, v, o, d_o, lse, dq, dk, dv, B, H, Hkv, N, d_qk, d_v, scale, causal,
+                    workspace, workspace_bytes, stream, ATTN_BWD_ALL);
 }
 
 int attn_bwd_ex(const void* q, const void* k, const void* v, const void* o, const void* d_o,
@@ -156,10 +185,11 @@ size_t attn_varlen_workspace_bytes(int B, int total_tokens, int H, int Hkv, int 
     return backward ? w.total_bwd : w.total_fwd;
 }
 
-int attn_varlen_fwd(const void* q, const void* k, const void* v, void* o, float* lse,
-                    const int* cu_seqlens, int B, int total_tokens, int H, int Hkv, int d_qk, int d_v,
-                    float scale, int causal, void* workspace, size_t workspace_bytes, void* stream)
+int attn_varlen_fwd_dtype(int dtype, const void* q, const void* k, const void* v, void* o, float* lse,
+                          const int* cu_seqlens, int B, int total_tokens, int H, int Hkv, int d_qk, int d_v,
+                          float scale, int causal, void* workspace, size_t workspace_bytes, void* stream)
 {
+    if (dtype != ATTN_BF16 && dtype != ATTN_F16) return ATTN_EUNSUPPORTED;
     if (!q || !k || !v || !o || !lse || !cu_seqlens || !workspace) return ATTN_EINVAL;
     if (int rc = check_varlen(B, total_tokens, H, Hkv, d_qk, d_v)) return rc;
     if (!(scale > 0.0f) || !(scale < 1e30f)) return ATTN_EINVAL;
@@ -174,15 +204,25 @@ int attn_varlen_fwd(const void* q, const void* k, const void* v, void* o, float*
     a.plan = ws + w.plan_off;
     a.T = total_tokens;
     a.max_tiles = w.max_tiles;
+    a.f16 = dtype == ATTN_F16;
     const int rc = attn::launch_fwd(a);
     return rc == 0 ? ATTN_OK : (rc == -2 ? ATTN_EUNSUPPORTED : ATTN_ELAUNCH);
 }
 
-int attn_varlen_bwd(const void* q, const void* k, const void* v, const void* o, const void* d_o,
-                    const float* lse, void* dq, void* dk, void* dv,
+int attn_varlen_fwd(const void* q, const void* k, const void* v, void* o, float* lse,
                     const int* cu_seqlens, int B, int total_tokens, int H, int Hkv, int d_qk, int d_v,
                     float scale, int causal, void* workspace, size_t workspace_bytes, void* stream)
 {
+    return attn_varlen_fwd_dtype(ATTN_BF16, q, k, v, o, lse, cu_seqlens, B, total_tokens, H, Hkv, d_qk, d_v, scale,
+                                 causal, workspace, workspace_bytes, stream);
+}
+
+int attn_varlen_bwd_dtype(int dtype, const void* q, const void* k, const void* v, const void* o, const void* d_o,
+                          const float* lse, void* dq, void* dk, void* dv,
+                          const int* cu_seqlens, int B, int total_tokens, int H, int Hkv, int d_qk, int d_v,
+                          float scale, int causal, void* workspace, size_t workspace_bytes, void* stream)
+{
+    if (dtype != ATTN_BF16 && dtype != ATTN_F16) return ATTN_EUNSUPPORTED;
     if (!q || !k || !v || !o || !d_o || !lse || !dq || !dk || !dv || !cu_seqlens || !workspace) return ATTN_EINVAL;
     if (int rc = check_varlen(B, total_tokens, H, Hkv, d_qk, d_v)) return rc;
     if (!(scale > 0.0f) || !(scale < 1e30f)) return ATTN_EINVAL;
@@ -200,8 +240,18 @@ int attn_varlen_bwd(const void* q, const void* k, const void* v, const void* o, 
     a.plan = ws + w.plan_off;
     a.T = total_tokens;
     a.max_tiles = w.max_tiles;
+    a.f16 = dtype == ATTN_F16;
     const int rc = attn::launch_bwd(a);
     return rc == 0 ? ATTN_OK : (rc == -2 ? ATTN_EUNSUPPORTED : ATTN_ELAUNCH);
+}
+
+int attn_varlen_bwd(const void* q, const void* k, const void* v, const void* o, const void* d_o,
+                    const float* lse, void* dq, void* dk, void* dv,
+                    const int* cu_seqlens, int B, int total_tokens, int H, int Hkv, int d_qk, int d_v,
+                    float scale, int causal, void* workspace, size_t workspace_bytes, void* stream)
+{
+    return attn_varlen_bwd_dtype(ATTN_BF16, q, k, v, o, d_o, lse, dq, dk, dv, cu_seqlens, B, total_tokens, H, Hkv,
+                                 d_qk, d_v, scale, causal, workspace, workspace_bytes, stream);
 }
 
 const char* attn_strerror(int code)

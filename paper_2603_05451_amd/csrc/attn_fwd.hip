@@ -31,45 +31,40 @@ constexpr int FWD_NT = 256;
 #ifndef ATTN_FWD_OCC192
 #define ATTN_FWD_OCC192 2
 #endif
+// ---- bf16 kernels
+#define ATTN_ELEM bf16
+#define ATTN_ELEM8 bf16x8
+#define ATTN_ELEM4 bf16x4
+#include "elem.inc"
+#undef ATTN_ELEM
+#undef ATTN_ELEM8
+#undef ATTN_ELEM4
 #define ATTN_VARLEN 0
 #include "attn_fwd_kernel.inc"
 #undef ATTN_VARLEN
 #define ATTN_VARLEN 1
 #include "attn_fwd_kernel.inc"
 #undef ATTN_VARLEN
+#include "attn_fwd_launch.inc"
 
-template <int DQK, int DV, bool CAUSAL>
-static int launch_fwd_t(const FwdArgs& a)
-{
-    constexpr int smem = 2 * FWD_BN * (DQK + DV) * 2;
-    hipError_t e;
-    if (a.plan) {
-        auto kern = attn_fwd_varlen_kernel<DQK, DV, CAUSAL>;
-        static LdsOptIn lds;
-        if (!lds.allow(kern, smem)) return -3;
-        e = launch_kernel(kern, dim3(a.max_tiles * a.H), dim3(FWD_NT), smem, a.stream,
-                          (const bf16*)a.q, (const bf16*)a.k, (const bf16*)a.v, (bf16*)a.o, a.lse,
-                          a.H, a.Hkv, a.scale * kLog2e, (const int4*)a.plan, a.T, a.max_tiles);
-    } else {
-        auto kern = attn_fwd_kernel<DQK, DV, CAUSAL>;
-        static LdsOptIn lds;
-        if (!lds.allow(kern, smem)) return -3;
-        e = launch_kernel(kern, dim3(a.B * a.H * (a.N / FWD_BM)), dim3(FWD_NT), smem, a.stream,
-                          (const bf16*)a.q, (const bf16*)a.k, (const bf16*)a.v, (bf16*)a.o, a.lse,
-                          a.H, a.Hkv, a.N, a.scale * kLog2e);
-    }
-    return e == hipSuccess ? 0 : -3;
-}
+// ---- fp16 kernels: the same text, element type _Float16 (v_mfma_f32_32x32x16_f16)
+namespace f16k {
+#define ATTN_ELEM f16
+#define ATTN_ELEM8 f16x8
+#define ATTN_ELEM4 f16x4
+#include "elem.inc"
+#undef ATTN_ELEM
+#undef ATTN_ELEM8
+#undef ATTN_ELEM4
+#define ATTN_VARLEN 0
+#include "attn_fwd_kernel.inc"
+#undef ATTN_VARLEN
+#define ATTN_VARLEN 1
+#include "attn_fwd_kernel.inc"
+#undef ATTN_VARLEN
+#include "attn_fwd_launch.inc"
+}  // namespace f16k
 
-int launch_fwd(const FwdArgs& a)
-{
-    if (a.d_qk == 64 && a.d_v == 64)
-        return a.causal ? launch_fwd_t<64, 64, true>(a) : launch_fwd_t<64, 64, false>(a);
-    if (a.d_qk == 128 && a.d_v == 128)
-        return a.causal ? launch_fwd_t<128, 128, true>(a) : launch_fwd_t<128, 128, false>(a);
-    if (a.d_qk == 192 && a.d_v == 128)
-        return a.causal ? launch_fwd_t<192, 128, true>(a) : launch_fwd_t<192, 128, false>(a);
-    return -2;
-}
+int launch_fwd(const FwdArgs& a) { return a.f16 ? f16k::launch_fwd_dims(a) : launch_fwd_dims(a); }
 
 }  // namespace attn

@@ -12,6 +12,9 @@ typedef __bf16 bf16;
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
 typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+typedef _Float16 f16;
+typedef __attribute__((ext_vector_type(8))) _Float16 f16x8;
+typedef __attribute__((ext_vector_type(4))) _Float16 f16x4;
 typedef __attribute__((ext_vector_type(4))) short s16x4;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __attribute__((ext_vector_type(4))) float f32x4;
@@ -31,6 +34,11 @@ constexpr float kRescaleTau = 8.0f;
 __device__ __forceinline__ f32x16 mfma32(bf16x8 a, bf16x8 b, f32x16 c)
 {
     return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+}
+
+__device__ __forceinline__ f32x16 mfma32(f16x8 a, f16x8 b, f32x16 c)      // v_mfma_f32_32x32x16_f16, same layouts
+{
+    return __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b, c, 0, 0, 0);
 }
 
 // Row of a 32x32 accumulator register r for lane half h.
@@ -155,7 +163,7 @@ struct TileCopy {
         }
     }
     // gtile must be wave-uniform (it is passed in SGPRs)
-    __device__ __forceinline__ void issue(int t, const bf16* gtile, ATTN_LDS char* lds_tile) const
+    __device__ __forceinline__ void issue(int t, const void* gtile, ATTN_LDS char* lds_tile) const
     {
         const uint32_t m0 = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)lds_tile) + loff[t];
         const uint64_t base = (uint64_t)gtile;
@@ -165,7 +173,7 @@ struct TileCopy {
         asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
                      :: "s"(m0), "v"(goff[t]), "s"(sbase) : "memory");
     }
-    __device__ __forceinline__ void issue_all(const bf16* gtile, ATTN_LDS char* lds_tile) const
+    __device__ __forceinline__ void issue_all(const void* gtile, ATTN_LDS char* lds_tile) const
     {
 #pragma unroll
         for (int t = 0; t < N; ++t) issue(t, gtile, lds_tile);
@@ -174,7 +182,7 @@ struct TileCopy {
     // later row re-reads the last valid one, so nothing outside the tensor is touched.  Per-lane
     // address arithmetic; meant for the one ragged tile at the end of a sequence.  `tid` and the
     // row stride must be those given to init.
-    __device__ __forceinline__ void issue_all_guarded(const bf16* gtile, ATTN_LDS char* lds_tile,
+    __device__ __forceinline__ void issue_all_guarded(const void* gtile, ATTN_LDS char* lds_tile,
                                                       int valid_rows, int64_t gstride, int tid) const
     {
         constexpr int CPR = D / 8;
@@ -218,22 +226,11 @@ __device__ __forceinline__ void pin_ready(T& x) { asm volatile("" : "+v"(x)); }
 // transcendental work may move across (so softmax arithmetic can fill MFMA shadows).
 __device__ __forceinline__ void sched_fence() { __builtin_amdgcn_sched_barrier(0x2 | 0x4 | 0x400); }
 
-__device__ __forceinline__ bf16x8 lds_read_b128(const ATTN_LDS char* p)
-{
-    return *(const ATTN_LDS bf16x8*)p;
-}
-
 // ds_read_b64_tr_b16: within each group of 16 lanes, lane i receives element (i % 4) of the
 // 8-byte rows fetched by lanes i/4, 4 + i/4, 8 + i/4, 12 + i/4 of the group.
-__device__ __forceinline__ bf16x4 lds_read_tr(const ATTN_LDS char* p)
+__device__ __forceinline__ s16x4 lds_read_tr_bits(const ATTN_LDS char* p)
 {
-    s16x4 r = __builtin_amdgcn_ds_read_tr16_b64_v4i16((ATTN_LDS s16x4*)p);
-    return __builtin_bit_cast(bf16x4, r);
-}
-
-__device__ __forceinline__ bf16x8 cat4(bf16x4 a, bf16x4 b)
-{
-    return __builtin_shufflevector(a, b, 0, 1, 2, 3, 4, 5, 6, 7);
+    return __builtin_amdgcn_ds_read_tr16_b64_v4i16((ATTN_LDS s16x4*)p);
 }
 
 }  // namespace attn

@@ -18,6 +18,7 @@ struct FwdArgs {
     // of the plan table (an upper bound on the number of 128-row tiles)
     const void* plan = nullptr;
     int T = 0, max_tiles = 0;
+    bool f16 = false;   // 16-bit storage type of q, k, v, o: bf16 (default) or IEEE fp16
 };
 
 struct BwdArgs {
@@ -34,6 +35,7 @@ struct BwdArgs {
     int phases;   // bit mask: 1 prepare, 2 dK/dV kernel, 4 dQ kernel
     const void* plan = nullptr;   // variable-length mode, as in FwdArgs
     int T = 0, max_tiles = 0;
+    bool f16 = false;             // as in FwdArgs
 };
 
 // Launch through hipLaunchKernel so that the status returned belongs to THIS launch (the
