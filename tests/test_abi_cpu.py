@@ -116,3 +116,16 @@ def test_varlen_workspace_and_validation(L):
     assert call(p, p, p, p, p, p, 3, 1000, 4, 2, 80, 80, 0.1, 0, w, 1 << 20, None) == A.ATTN_EUNSUPPORTED
     assert call(p, p, p, p, p, p, 3, 1000, 4, 2, 128, 128, -1.0, 0, w, 1 << 20, None) == A.ATTN_EINVAL
     assert L.attn_varlen_bwd(p, p, p, p, p, p, p, p, p, p, 3, 1000, 4, 2, 128, 128, 0.1, 0, w, 256, None) == A.ATTN_EINVAL
+
+
+def test_varlen_workload_recipe_is_deterministic():
+    from paper_2603_05451_amd import inputs as I
+    w = I.VARLEN_MIX
+    a, b = w.lengths(), w.lengths()
+    assert a == b and len(a) == w.B and min(a) >= w.lo and max(a) <= w.hi
+    x = I.make_varlen_inputs(w, with_do=False)
+    T = sum(a)
+    assert tuple(x["q"].shape) == (T, w.H, w.dqk) and tuple(x["k"].shape) == (T, w.Hkv, w.dqk)
+    cu = x["cu_seqlens"].tolist()
+    assert cu[0] == 0 and cu[-1] == T and [cu[i + 1] - cu[i] for i in range(w.B)] == a
+    assert w.fwd_flops() == sum(2.0 * n * n * (w.dqk + w.dv) * w.H for n in a) / 2      # causal

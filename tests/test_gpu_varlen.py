@@ -193,3 +193,33 @@ def test_varlen_many_short_sequences(oracle):
         # exactly-zero reference rows)
         ok = lambda got, ref: (np.abs(got - ref) <= 2e-2 + 2.0 ** -8 * np.abs(ref)).all()
         assert ok(o[s][None], ro) and ok(dq[s][None], rdq) and ok(dk[s][None], rdk) and ok(dv[s][None], rdv)
+
+
+def test_plan_table_lists_every_tile_once_longest_first():
+    """The plan kernel's output (first section of the workspace): one entry per 128-row tile of every
+    non-empty sequence, sequences with more tiles before sequences with fewer, a sequence's tiles
+    contiguous and from last to first, the rest of the table marked unused."""
+    import paper_2603_05451_amd as A
+    rng = np.random.default_rng(3)
+    lengths = [int(n) for n in np.concatenate([rng.integers(0, 700, 300), [0, 1, 128, 129, 4096, 5000]])]
+    rng.shuffle(lengths)
+    cu = np.concatenate([[0], np.cumsum(lengths)]).astype(np.int32)
+    T, B, H, d = int(cu[-1]), len(lengths), 1, 64
+    q = torch.zeros(T, H, d, dtype=torch.bfloat16, device="cuda")
+    ws = torch.empty(A.attn_varlen_workspace_bytes(B, T, H, H, d, d, False), dtype=torch.uint8, device="cuda")
+    A.attn_varlen_fwd(q, q, q, torch.from_numpy(cu).cuda(), 0.125, False, workspace=ws)
+    torch.cuda.synchronize()
+    max_tiles = T // 128 + B
+    plan = ws[:max_tiles * 16].view(torch.int32).reshape(max_tiles, 4).cpu().numpy()
+    want = {(int(cu[b]), n, t) for b, n in enumerate(lengths) for t in range((n + 127) // 128)}
+    used = plan[plan[:, 3] == 1]
+    assert len(used) == len(want) and {tuple(int(x) for x in e[:3]) for e in used} == want
+    assert (plan[len(used):] == 0).all()                                  # valid entries first, then zeros
+    tiles_of = (used[:, 1] + 127) // 128
+    assert (np.diff(tiles_of) <= 0).all()                                 # most tiles first
+    i = 0
+    while i < len(used):                                                  # runs: one sequence, tiles nt-1 .. 0
+        nt = int(tiles_of[i])
+        run = used[i:i + nt]
+        assert (run[:, 0] == run[0, 0]).all() and list(run[:, 2]) == list(range(nt - 1, -1, -1))
+        i += nt
