@@ -84,8 +84,8 @@ def write_table(path, workloads, n=10, warm=5):
     import torch
     import paper_2603_05451_amd as A
     from paper_2603_05451_amd import inputs as I
-    rows = ["| workload | B | H/Hkv | N | d_qk/d_v | causal | fwd ms | fwd TFLOP/s | % peak | bwd ms | bwd TFLOP/s | % peak |",
-            "|---|---|---|---|---|---|---|---|---|---|---|---|"]
+    rows = ["| workload | B | H/Hkv | N | d_qk/d_v | causal | fwd ms | fwd TFLOP/s | % peak | fwd % of 8 TB/s | bwd ms | bwd TFLOP/s | % peak | bwd % of 8 TB/s |",
+            "|---|---|---|---|---|---|---|---|---|---|---|---|---|---|"]
     for w in workloads:
         x = I.make_inputs(w)
         q, k, v, do = (x[n].cuda() for n in ("q", "k", "v", "do"))
@@ -99,8 +99,15 @@ def write_table(path, workloads, n=10, warm=5):
             fwd(); bwd()
         mf, mb = event_ms(fwd, n), event_ms(bwd, n)
         tf, tb = w.fwd_flops() / mf / 1e9, w.bwd_flops() / mb / 1e9
+        # compulsory HBM traffic: every input read once, every output written once (the short
+        # sequences are bound by it, or by launch latency, not by the matrix cores)
+        rows_q, rows_k = w.B * w.N * w.H, w.B * w.N * w.Hkv
+        byt_f = 2 * (rows_q * (w.dqk + w.dv) + rows_k * (w.dqk + w.dv)) + 4 * rows_q
+        byt_b = 2 * (rows_q * (2 * w.dqk + 3 * w.dv) + 2 * rows_k * (w.dqk + w.dv)) + 4 * rows_q
+        hf, hb = byt_f / mf / 1e6 / 8000, byt_b / mb / 1e6 / 8000      # GB/s over the 8000 GB/s peak
         rows.append(f"| {w.name} | {w.B} | {w.H}/{w.Hkv} | {w.N} | {w.dqk}/{w.dv} | {int(w.causal)} | {mf:.3f} | {tf:.0f} | "
-                    f"{100 * tf / PEAK_BF16_TFLOPS:.1f} | {mb:.3f} | {tb:.0f} | {100 * tb / PEAK_BF16_TFLOPS:.1f} |")
+                    f"{100 * tf / PEAK_BF16_TFLOPS:.1f} | {100 * hf:.1f} | {mb:.3f} | {tb:.0f} | "
+                    f"{100 * tb / PEAK_BF16_TFLOPS:.1f} | {100 * hb:.1f} |")
         del q, k, v, do, o, lse, dq, dk, dv, ws
     with open(path, "w") as f:
         f.write("\n".join(rows) + "\n")
