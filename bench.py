@@ -128,7 +128,7 @@ def write_varlen_table(path, workloads, n=10, warm=5):
         o = torch.empty((T, w.H, w.dv), dtype=torch.bfloat16, device="cuda")
         lse = torch.empty((w.H, T), dtype=torch.float32, device="cuda")
         dq, dk, dv = torch.empty_like(q), torch.empty_like(k), torch.empty_like(v)
-        ws = torch.empty(A.attn_varlen_workspace_bytes(w.B, T, w.H, w.Hkv, w.dqk, w.dv, True), dtype=torch.uint8, device="cuda")
+        ws = torch.empty(A.attn_varlen_workspace_bytes(w.B, T, T, w.H, w.Hkv, w.dqk, w.dv, True), dtype=torch.uint8, device="cuda")
         fwd = lambda: A.attn_varlen_fwd(q, k, v, cu, w.scale, w.causal, o, lse, ws)
         bwd = lambda: A.attn_varlen_bwd(q, k, v, o, do, lse, cu, w.scale, w.causal, dq, dk, dv, ws)
         for _ in range(warm):

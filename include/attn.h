@@ -99,33 +99,42 @@ int attn_bwd_phases(const void* q, const void* k, const void* v, const void* o, 
  * D and the base-2 LSE, [B,H,N] fp32 each (256-byte aligned sections). */
 size_t attn_bwd_workspace_bytes(int B, int H, int Hkv, int N, int d_qk, int d_v);
 
-/* Variable sequence lengths (paper Sec. 3.3): B sequences of different lengths packed back to
- * back, self-attention inside each sequence only.
- *   layouts  q, o, d_o, dq : [T, H, d]    k, dk : [T, Hkv, d_qk]    v, dv : [T, Hkv, d_v]   bf16
- *            lse           : [H, T] fp32
- *            cu_seqlens    : [B + 1] int32, DEVICE memory, cu[0] = 0, non-decreasing,
- *                            cu[B] = T = total_tokens; sequence b owns rows cu[b] .. cu[b+1]-1.
- *                            Any length >= 0 is allowed (no multiple-of-128 requirement).
- *   causal != 0: inside a sequence, key j is visible to query i iff j <= i.
- *   The host never reads cu_seqlens: a small kernel turns it into a table of 128-row tiles,
- *   sequences with the most tiles first (the longest-processing-time-first order of Sec. 3.3),
- *   and the attention kernels are launched over an upper bound of T/128 + B tiles per head.
+/* Variable sequence lengths (paper Sec. 3.3: a list of query and key/value sequence lengths per
+ * batch): B sequences packed back to back, attention inside each sequence only; a sequence's
+ * number of queries and number of keys may differ (cross-attention, decoding against a cache).
+ *   layouts  q, o, d_o, dq : [Tq, H, d]    k, dk : [Tk, Hkv, d_qk]    v, dv : [Tk, Hkv, d_v]   bf16
+ *            lse           : [H, Tq] fp32
+ *            cu_seqlens_q  : [B + 1] int32, DEVICE memory, cu[0] = 0, non-decreasing,
+ *                            cu[B] = Tq = total_q; sequence b owns query rows cu[b] .. cu[b+1]-1.
+ *            cu_seqlens_k  : the same for the key/value rows, cu[B] = Tk = total_k; may be the same
+ *                            pointer as cu_seqlens_q (self-attention).
+ *                            Any length >= 0 is allowed (no multiple-of-128 requirement), except that
+ *                            a sequence with queries must have at least one key, and under a causal
+ *                            mask at least as many keys as queries.
+ *   causal != 0: the last query of a sequence is aligned with its last key: key j is visible to
+ *   query i iff j <= i + (keys - queries) of that sequence; j <= i for self-attention.
+ *   The host never reads the lengths: a small kernel turns them into tables of 128-row tiles,
+ *   sequences with the longest loop per tile first (the longest-processing-time-first order of
+ *   Sec. 3.3), and the attention kernels are launched over upper bounds of total_q/128 + B query
+ *   tiles per head and total_k/128 + B key tiles per key/value head.
  *   workspace: attn_varlen_workspace_bytes(..., backward) bytes, 256-byte aligned; the forward
  *   call needs the backward = 0 size, the backward call the backward = 1 size.  Contents on entry
  *   are ignored.  All other conventions (device pointers, stream, alignment, head dims, error
  *   codes, nothing enqueued on error) are those of attn_fwd_ex / attn_bwd_ex.  Behaviour is
- *   undefined if cu_seqlens violates the conditions above. */
-size_t attn_varlen_workspace_bytes(int B, int total_tokens, int H, int Hkv, int d_qk, int d_v, int backward);
+ *   undefined if the cu_seqlens arrays violate the conditions above. */
+size_t attn_varlen_workspace_bytes(int B, int total_q, int total_k, int H, int Hkv, int d_qk, int d_v, int backward);
 int attn_varlen_fwd(const void* q, const void* k, const void* v, void* o, float* lse,
-                    const int* cu_seqlens, int B, int total_tokens, int H, int Hkv, int d_qk, int d_v,
+                    const int* cu_seqlens_q, const int* cu_seqlens_k, int B, int total_q, int total_k,
+                    int H, int Hkv, int d_qk, int d_v,
                     float scale, int causal, void* workspace, size_t workspace_bytes, void* stream);
 /* Backward of attn_varlen_fwd (paper Sec. 2.1 second display, per sequence): o and lse must be that
  * call's outputs for the same arguments; dk and dv are summed over the query heads of each group.
- * Rows of dq, dk, dv that belong to no sequence do not exist (T = cu[B]); every existing row is
- * written.  No atomics: bit-reproducible like attn_bwd. */
+ * Every row of dq, dk, dv is written (dk = dv = 0 for the keys of a sequence without queries).
+ * No atomics: bit-reproducible like attn_bwd. */
 int attn_varlen_bwd(const void* q, const void* k, const void* v, const void* o, const void* d_o,
                     const float* lse, void* dq, void* dk, void* dv,
-                    const int* cu_seqlens, int B, int total_tokens, int H, int Hkv, int d_qk, int d_v,
+                    const int* cu_seqlens_q, const int* cu_seqlens_k, int B, int total_q, int total_k,
+                    int H, int Hkv, int d_qk, int d_v,
                     float scale, int causal, void* workspace, size_t workspace_bytes, void* stream);
 
 /* The same four operations on IEEE fp16 storage (the paper's benchmarks cover FP16 and BF16
@@ -142,11 +151,13 @@ int attn_bwd_dtype(int dtype, const void* q, const void* k, const void* v, const
                    int B, int H, int Hkv, int N, int d_qk, int d_v, float scale, int causal,
                    void* workspace, size_t workspace_bytes, void* stream);
 int attn_varlen_fwd_dtype(int dtype, const void* q, const void* k, const void* v, void* o, float* lse,
-                          const int* cu_seqlens, int B, int total_tokens, int H, int Hkv, int d_qk, int d_v,
+                          const int* cu_seqlens_q, const int* cu_seqlens_k, int B, int total_q, int total_k,
+                          int H, int Hkv, int d_qk, int d_v,
                           float scale, int causal, void* workspace, size_t workspace_bytes, void* stream);
 int attn_varlen_bwd_dtype(int dtype, const void* q, const void* k, const void* v, const void* o, const void* d_o,
                           const float* lse, void* dq, void* dk, void* dv,
-                          const int* cu_seqlens, int B, int total_tokens, int H, int Hkv, int d_qk, int d_v,
+                          const int* cu_seqlens_q, const int* cu_seqlens_k, int B, int total_q, int total_k,
+                          int H, int Hkv, int d_qk, int d_v,
                           float scale, int causal, void* workspace, size_t workspace_bytes, void* stream);
 
 /* Software 2^x of paper Sec. 3.1.3 (range reduction + degree-n minimax polynomial, p0 = 1, Horner

@@ -51,15 +51,15 @@ def lib():
         L.attn_fwd_dtype.restype = i
         L.attn_bwd_dtype.argtypes = [i] + [vp] * 9 + [i, i, i, i, i, i, f, i, vp, sz, vp]
         L.attn_bwd_dtype.restype = i
-        L.attn_varlen_fwd_dtype.argtypes = [i] + [vp] * 6 + [i, i, i, i, i, i, f, i, vp, sz, vp]
+        L.attn_varlen_fwd_dtype.argtypes = [i] + [vp] * 7 + [i] * 7 + [f, i, vp, sz, vp]
         L.attn_varlen_fwd_dtype.restype = i
-        L.attn_varlen_bwd_dtype.argtypes = [i] + [vp] * 10 + [i, i, i, i, i, i, f, i, vp, sz, vp]
+        L.attn_varlen_bwd_dtype.argtypes = [i] + [vp] * 11 + [i] * 7 + [f, i, vp, sz, vp]
         L.attn_varlen_bwd_dtype.restype = i
-        L.attn_varlen_workspace_bytes.argtypes = [i] * 7
+        L.attn_varlen_workspace_bytes.argtypes = [i] * 8
         L.attn_varlen_workspace_bytes.restype = sz
-        L.attn_varlen_fwd.argtypes = [vp] * 6 + [i, i, i, i, i, i, f, i, vp, sz, vp]
+        L.attn_varlen_fwd.argtypes = [vp] * 7 + [i] * 7 + [f, i, vp, sz, vp]
         L.attn_varlen_fwd.restype = i
-        L.attn_varlen_bwd.argtypes = [vp] * 10 + [i, i, i, i, i, i, f, i, vp, sz, vp]
+        L.attn_varlen_bwd.argtypes = [vp] * 11 + [i] * 7 + [f, i, vp, sz, vp]
         L.attn_varlen_bwd.restype = i
         L.attn_exp2_emulated.argtypes = [vp, vp, sz, i, vp]
         L.attn_exp2_emulated.restype = i
@@ -145,37 +145,41 @@ def attn_fwd(q, k, v, scale, causal, o=None, lse=None, stream=None):
     return o, lse
 
 
-def attn_varlen_workspace_bytes(B, total_tokens, H, Hkv, d_qk, d_v, backward) -> int:
-    return int(lib().attn_varlen_workspace_bytes(B, total_tokens, H, Hkv, d_qk, d_v, int(bool(backward))))
+def attn_varlen_workspace_bytes(B, total_q, total_k, H, Hkv, d_qk, d_v, backward) -> int:
+    return int(lib().attn_varlen_workspace_bytes(B, total_q, total_k, H, Hkv, d_qk, d_v, int(bool(backward))))
 
 
-def _dev_cu(cu, B):
+def _dev_cu(cu, B, name="cu_seqlens"):
     import torch
     if not (cu.is_cuda and cu.dtype == torch.int32 and cu.is_contiguous() and tuple(cu.shape) == (B + 1,)):
-        raise ValueError("cu_seqlens must be a contiguous int32 CUDA tensor [B+1]")
+        raise ValueError(f"{name} must be a contiguous int32 CUDA tensor [B+1]")
     return ctypes.c_void_p(cu.data_ptr())
 
 
-def attn_varlen_fwd(q, k, v, cu_seqlens, scale, causal, o=None, lse=None, workspace=None, stream=None):
-    """Packed variable-length batch: q [T,H,d_qk], k [T,Hkv,d_qk], v [T,Hkv,d_v] bf16, cu_seqlens [B+1]
-    int32, all on the GPU -> (o [T,H,d_v] bf16, lse [H,T] fp32)."""
+def attn_varlen_fwd(q, k, v, cu_seqlens, scale, causal, o=None, lse=None, workspace=None, stream=None,
+                    cu_seqlens_k=None):
+    """Packed variable-length batch: q [Tq,H,d_qk], k [Tk,Hkv,d_qk], v [Tk,Hkv,d_v] bf16 (or all fp16),
+    cu_seqlens [B+1] int32 (query rows; also the key rows unless cu_seqlens_k is given), all on the
+    GPU -> (o [Tq,H,d_v], lse [H,Tq] fp32)."""
     import torch
     T, H, dqk = q.shape
-    Hkv, dv = k.shape[1], v.shape[2]
+    Tk, Hkv, dv = k.shape[0], k.shape[1], v.shape[2]
     B = cu_seqlens.numel() - 1
+    if cu_seqlens_k is None:
+        cu_seqlens_k = cu_seqlens
     if o is None:
         o = torch.empty((T, H, dv), dtype=q.dtype, device=q.device)
     if lse is None:
         lse = torch.empty((H, T), dtype=torch.float32, device=q.device)
     if not (lse.is_cuda and lse.dtype == torch.float32 and lse.is_contiguous() and tuple(lse.shape) == (H, T)):
-        raise ValueError("lse must be a contiguous fp32 CUDA tensor [H,T]")
-    need = attn_varlen_workspace_bytes(B, T, H, Hkv, dqk, dv, False)
+        raise ValueError("lse must be a contiguous fp32 CUDA tensor [H,Tq]")
+    need = attn_varlen_workspace_bytes(B, T, Tk, H, Hkv, dqk, dv, False)
     if workspace is None:
         workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=q.device)
     code = _dtype_code(q)
-    args = (_dev_bf16(q, "q", like=q), _dev_bf16(k, "k", (T, Hkv, dqk), q), _dev_bf16(v, "v", (T, Hkv, dv), q),
+    args = (_dev_bf16(q, "q", like=q), _dev_bf16(k, "k", (Tk, Hkv, dqk), q), _dev_bf16(v, "v", (Tk, Hkv, dv), q),
             _dev_bf16(o, "o", (T, H, dv), q), ctypes.c_void_p(lse.data_ptr()), _dev_cu(cu_seqlens, B),
-            B, T, H, Hkv, dqk, dv, float(scale), int(bool(causal)),
+            _dev_cu(cu_seqlens_k, B, "cu_seqlens_k"), B, T, Tk, H, Hkv, dqk, dv, float(scale), int(bool(causal)),
             ctypes.c_void_p(workspace.data_ptr()), workspace.numel(), _stream(stream))
     rc = lib().attn_varlen_fwd(*args) if code == ATTN_BF16 else lib().attn_varlen_fwd_dtype(code, *args)
     _check(rc)
@@ -183,26 +187,29 @@ def attn_varlen_fwd(q, k, v, cu_seqlens, scale, causal, o=None, lse=None, worksp
 
 
 def attn_varlen_bwd(q, k, v, o, d_o, lse, cu_seqlens, scale, causal, dq=None, dk=None, dv=None, workspace=None,
-                    stream=None):
-    """Backward of attn_varlen_fwd: returns (dq [T,H,d_qk], dk [T,Hkv,d_qk], dv [T,Hkv,d_v]) bf16."""
+                    stream=None, cu_seqlens_k=None):
+    """Backward of attn_varlen_fwd: returns (dq [Tq,H,d_qk], dk [Tk,Hkv,d_qk], dv [Tk,Hkv,d_v])."""
     import torch
     T, H, dqk = q.shape
-    Hkv, dv_ = k.shape[1], v.shape[2]
+    Tk, Hkv, dv_ = k.shape[0], k.shape[1], v.shape[2]
     B = cu_seqlens.numel() - 1
+    if cu_seqlens_k is None:
+        cu_seqlens_k = cu_seqlens
     dq = torch.empty_like(q) if dq is None else dq
     dk = torch.empty_like(k) if dk is None else dk
     dv = torch.empty_like(v) if dv is None else dv
-    need = attn_varlen_workspace_bytes(B, T, H, Hkv, dqk, dv_, True)
+    need = attn_varlen_workspace_bytes(B, T, Tk, H, Hkv, dqk, dv_, True)
     if workspace is None:
         workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=q.device)
     if not (lse.is_cuda and lse.dtype == torch.float32 and lse.is_contiguous() and tuple(lse.shape) == (H, T)):
-        raise ValueError("lse must be a contiguous fp32 CUDA tensor [H,T]")
+        raise ValueError("lse must be a contiguous fp32 CUDA tensor [H,Tq]")
     code = _dtype_code(q)
-    args = (_dev_bf16(q, "q", like=q), _dev_bf16(k, "k", (T, Hkv, dqk), q), _dev_bf16(v, "v", (T, Hkv, dv_), q),
+    args = (_dev_bf16(q, "q", like=q), _dev_bf16(k, "k", (Tk, Hkv, dqk), q), _dev_bf16(v, "v", (Tk, Hkv, dv_), q),
             _dev_bf16(o, "o", (T, H, dv_), q), _dev_bf16(d_o, "d_o", (T, H, dv_), q),
             ctypes.c_void_p(lse.data_ptr()), _dev_bf16(dq, "dq", (T, H, dqk), q),
-            _dev_bf16(dk, "dk", (T, Hkv, dqk), q), _dev_bf16(dv, "dv", (T, Hkv, dv_), q),
-            _dev_cu(cu_seqlens, B), B, T, H, Hkv, dqk, dv_, float(scale), int(bool(causal)),
+            _dev_bf16(dk, "dk", (Tk, Hkv, dqk), q), _dev_bf16(dv, "dv", (Tk, Hkv, dv_), q),
+            _dev_cu(cu_seqlens, B), _dev_cu(cu_seqlens_k, B, "cu_seqlens_k"), B, T, Tk, H, Hkv, dqk, dv_,
+            float(scale), int(bool(causal)),
             ctypes.c_void_p(workspace.data_ptr()), workspace.numel(), _stream(stream))
     rc = lib().attn_varlen_bwd(*args) if code == ATTN_BF16 else lib().attn_varlen_bwd_dtype(code, *args)
     _check(rc)

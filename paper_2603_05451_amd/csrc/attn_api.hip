@@ -149,97 +149,112 @@ int attn_bwd(const void* q, const void* k, const void* v, const void* o, const v
 
 namespace {
 
-int check_varlen(int B, int T, int H, int Hkv, int d_qk, int d_v)
+int check_varlen(int B, int Tq, int Tk, int H, int Hkv, int d_qk, int d_v)
 {
-    if (B <= 0 || T <= 0 || H <= 0 || Hkv <= 0) return ATTN_EINVAL;
+    if (B <= 0 || Tq <= 0 || Tk <= 0 || H <= 0 || Hkv <= 0) return ATTN_EINVAL;
     if (H % Hkv != 0) return ATTN_EINVAL;
     if (!dims_supported(d_qk, d_v)) return ATTN_EUNSUPPORTED;
-    if (((int64_t)T / 128 + B) * H > 0x7fffffffLL) return ATTN_EUNSUPPORTED;
+    if (((int64_t)Tq / 128 + B) * H > 0x7fffffffLL) return ATTN_EUNSUPPORTED;
+    if (((int64_t)Tk / 128 + B) * Hkv > 0x7fffffffLL) return ATTN_EUNSUPPORTED;
     if ((int64_t)H * (d_qk > d_v ? d_qk : d_v) * 2 * 128 > 0x7fffffffLL) return ATTN_EUNSUPPORTED;
     return ATTN_OK;
 }
 
+// Workspace of the variable-length calls: table of query tiles | table of key tiles | -D | LSE2
+// (forward: the first table only).  A table entry is 32 bytes.
 struct VarlenLayout {
-    int max_tiles;
-    size_t plan_off, d_off, lse2_off, total_fwd, total_bwd;
+    int max_tiles_q, max_tiles_k;
+    size_t plan_q_off, plan_k_off, d_off, lse2_off, total_fwd, total_bwd;
 };
 
-VarlenLayout varlen_layout(int B, int T, int H)
+VarlenLayout varlen_layout(int B, int Tq, int Tk, int H)
 {
     VarlenLayout w;
-    w.max_tiles = T / 128 + B;          // sum over sequences of ceil(len / 128) never exceeds this
-    w.plan_off = 0;
-    w.total_fwd = align_up((size_t)w.max_tiles * 16, 256);
-    w.d_off = w.total_fwd;
-    w.lse2_off = w.d_off + align_up((size_t)H * T * sizeof(float), 256);
-    w.total_bwd = w.lse2_off + align_up((size_t)H * T * sizeof(float), 256);
+    w.max_tiles_q = Tq / 128 + B;       // sum over sequences of ceil(len / 128) never exceeds this
+    w.max_tiles_k = Tk / 128 + B;
+    w.plan_q_off = 0;
+    w.total_fwd = align_up((size_t)w.max_tiles_q * 32, 256);
+    w.plan_k_off = w.total_fwd;
+    w.d_off = w.plan_k_off + align_up((size_t)w.max_tiles_k * 32, 256);
+    w.lse2_off = w.d_off + align_up((size_t)H * Tq * sizeof(float), 256);
+    w.total_bwd = w.lse2_off + align_up((size_t)H * Tq * sizeof(float), 256);
     return w;
 }
 
 }  // namespace
 
-size_t attn_varlen_workspace_bytes(int B, int total_tokens, int H, int Hkv, int d_qk, int d_v, int backward)
+size_t attn_varlen_workspace_bytes(int B, int total_q, int total_k, int H, int Hkv, int d_qk, int d_v, int backward)
 {
-    if (check_varlen(B, total_tokens, H, Hkv, d_qk, d_v) != ATTN_OK) return 0;
-    const VarlenLayout w = varlen_layout(B, total_tokens, H);
+    if (check_varlen(B, total_q, total_k, H, Hkv, d_qk, d_v) != ATTN_OK) return 0;
+    const VarlenLayout w = varlen_layout(B, total_q, total_k, H);
     return backward ? w.total_bwd : w.total_fwd;
 }
 
 int attn_varlen_fwd_dtype(int dtype, const void* q, const void* k, const void* v, void* o, float* lse,
-                          const int* cu_seqlens, int B, int total_tokens, int H, int Hkv, int d_qk, int d_v,
+                          const int* cu_seqlens_q, const int* cu_seqlens_k, int B, int total_q, int total_k,
+                          int H, int Hkv, int d_qk, int d_v,
                           float scale, int causal, void* workspace, size_t workspace_bytes, void* stream)
 {
     if (dtype != ATTN_BF16 && dtype != ATTN_F16) return ATTN_EUNSUPPORTED;
-    if (!q || !k || !v || !o || !lse || !cu_seqlens || !workspace) return ATTN_EINVAL;
-    if (int rc = check_varlen(B, total_tokens, H, Hkv, d_qk, d_v)) return rc;
+    if (!q || !k || !v || !o || !lse || !cu_seqlens_q || !cu_seqlens_k || !workspace) return ATTN_EINVAL;
+    if (int rc = check_varlen(B, total_q, total_k, H, Hkv, d_qk, d_v)) return rc;
     if (!(scale > 0.0f) || !(scale < 1e30f)) return ATTN_EINVAL;
     if (misaligned(q, 16) || misaligned(k, 16) || misaligned(v, 16) || misaligned(o, 16) ||
-        misaligned(lse, 4) || misaligned(cu_seqlens, 4) || misaligned(workspace, 256))
+        misaligned(lse, 4) || misaligned(cu_seqlens_q, 4) || misaligned(cu_seqlens_k, 4) || misaligned(workspace, 256))
         return ATTN_EINVAL;
-    const VarlenLayout w = varlen_layout(B, total_tokens, H);
+    const VarlenLayout w = varlen_layout(B, total_q, total_k, H);
     if (workspace_bytes < w.total_fwd) return ATTN_EINVAL;
     char* ws = static_cast<char*>(workspace);
-    if (attn::launch_varlen_plan(cu_seqlens, B, ws + w.plan_off, w.max_tiles, stream) != 0) return ATTN_ELAUNCH;
+    if (attn::launch_varlen_plan(cu_seqlens_q, cu_seqlens_k, B, ws + w.plan_q_off, w.max_tiles_q, nullptr, 0, stream) != 0)
+        return ATTN_ELAUNCH;
     attn::FwdArgs a{q, k, v, o, lse, B, H, Hkv, 0, d_qk, d_v, scale, causal != 0, stream};
-    a.plan = ws + w.plan_off;
-    a.T = total_tokens;
-    a.max_tiles = w.max_tiles;
+    a.plan = ws + w.plan_q_off;
+    a.T = total_q;
+    a.max_tiles = w.max_tiles_q;
     a.f16 = dtype == ATTN_F16;
     const int rc = attn::launch_fwd(a);
     return rc == 0 ? ATTN_OK : (rc == -2 ? ATTN_EUNSUPPORTED : ATTN_ELAUNCH);
 }
 
 int attn_varlen_fwd(const void* q, const void* k, const void* v, void* o, float* lse,
-                    const int* cu_seqlens, int B, int total_tokens, int H, int Hkv, int d_qk, int d_v,
+                    const int* cu_seqlens_q, const int* cu_seqlens_k, int B, int total_q, int total_k,
+                    int H, int Hkv, int d_qk, int d_v,
                     float scale, int causal, void* workspace, size_t workspace_bytes, void* stream)
 {
-    return attn_varlen_fwd_dtype(ATTN_BF16, q, k, v, o, lse, cu_seqlens, B, total_tokens, H, Hkv, d_qk, d_v, scale,
-                                 causal, workspace, workspace_bytes, stream);
+    return attn_varlen_fwd_dtype(ATTN_BF16, q, k, v, o, lse, cu_seqlens_q, cu_seqlens_k, B, total_q, total_k,
+                                 H, Hkv, d_qk, d_v, scale, causal, workspace, workspace_bytes, stream);
 }
 
 int attn_varlen_bwd_dtype(int dtype, const void* q, const void* k, const void* v, const void* o, const void* d_o,
                           const float* lse, void* dq, void* dk, void* dv,
-                          const int* cu_seqlens, int B, int total_tokens, int H, int Hkv, int d_qk, int d_v,
+                          const int* cu_seqlens_q, const int* cu_seqlens_k, int B, int total_q, int total_k,
+                          int H, int Hkv, int d_qk, int d_v,
                           float scale, int causal, void* workspace, size_t workspace_bytes, void* stream)
 {
     if (dtype != ATTN_BF16 && dtype != ATTN_F16) return ATTN_EUNSUPPORTED;
-    if (!q || !k || !v || !o || !d_o || !lse || !dq || !dk || !dv || !cu_seqlens || !workspace) return ATTN_EINVAL;
-    if (int rc = check_varlen(B, total_tokens, H, Hkv, d_qk, d_v)) return rc;
+    if (!q || !k || !v || !o || !d_o || !lse || !dq || !dk || !dv || !cu_seqlens_q || !cu_seqlens_k || !workspace)
+        return ATTN_EINVAL;
+    if (int rc = check_varlen(B, total_q, total_k, H, Hkv, d_qk, d_v)) return rc;
     if (!(scale > 0.0f) || !(scale < 1e30f)) return ATTN_EINVAL;
     const void* ptrs[] = {q, k, v, o, d_o, dq, dk, dv};
     for (const void* p : ptrs)
         if (misaligned(p, 16)) return ATTN_EINVAL;
-    if (misaligned(lse, 4) || misaligned(cu_seqlens, 4) || misaligned(workspace, 256)) return ATTN_EINVAL;
-    const VarlenLayout w = varlen_layout(B, total_tokens, H);
+    if (misaligned(lse, 4) || misaligned(cu_seqlens_q, 4) || misaligned(cu_seqlens_k, 4) || misaligned(workspace, 256))
+        return ATTN_EINVAL;
+    const VarlenLayout w = varlen_layout(B, total_q, total_k, H);
     if (workspace_bytes < w.total_bwd) return ATTN_EINVAL;
     char* ws = static_cast<char*>(workspace);
-    if (attn::launch_varlen_plan(cu_seqlens, B, ws + w.plan_off, w.max_tiles, stream) != 0) return ATTN_ELAUNCH;
+    if (attn::launch_varlen_plan(cu_seqlens_q, cu_seqlens_k, B, ws + w.plan_q_off, w.max_tiles_q,
+                                 ws + w.plan_k_off, w.max_tiles_k, stream) != 0)
+        return ATTN_ELAUNCH;
     attn::BwdArgs a{q, k, v, o, d_o, lse, dq, dk, dv, B, H, Hkv, 0, d_qk, d_v, scale, causal != 0,
                     reinterpret_cast<float*>(ws + w.d_off), reinterpret_cast<float*>(ws + w.lse2_off),
                     stream, ATTN_BWD_ALL};
-    a.plan = ws + w.plan_off;
-    a.T = total_tokens;
-    a.max_tiles = w.max_tiles;
+    a.plan = ws + w.plan_q_off;
+    a.T = total_q;
+    a.max_tiles = w.max_tiles_q;
+    a.plan_k = ws + w.plan_k_off;
+    a.max_tiles_k = w.max_tiles_k;
     a.f16 = dtype == ATTN_F16;
     const int rc = attn::launch_bwd(a);
     return rc == 0 ? ATTN_OK : (rc == -2 ? ATTN_EUNSUPPORTED : ATTN_ELAUNCH);
@@ -247,11 +262,13 @@ int attn_varlen_bwd_dtype(int dtype, const void* q, const void* k, const void* v
 
 int attn_varlen_bwd(const void* q, const void* k, const void* v, const void* o, const void* d_o,
                     const float* lse, void* dq, void* dk, void* dv,
-                    const int* cu_seqlens, int B, int total_tokens, int H, int Hkv, int d_qk, int d_v,
+                    const int* cu_seqlens_q, const int* cu_seqlens_k, int B, int total_q, int total_k,
+                    int H, int Hkv, int d_qk, int d_v,
                     float scale, int causal, void* workspace, size_t workspace_bytes, void* stream)
 {
-    return attn_varlen_bwd_dtype(ATTN_BF16, q, k, v, o, d_o, lse, dq, dk, dv, cu_seqlens, B, total_tokens, H, Hkv,
-                                 d_qk, d_v, scale, causal, workspace, workspace_bytes, stream);
+    return attn_varlen_bwd_dtype(ATTN_BF16, q, k, v, o, d_o, lse, dq, dk, dv, cu_seqlens_q, cu_seqlens_k, B,
+                                 total_q, total_k, H, Hkv, d_qk, d_v, scale, causal, workspace, workspace_bytes,
+                                 stream);
 }
 
 const char* attn_strerror(int code)

@@ -1,71 +1,68 @@
-// Plan table of the variable-length entry points (paper Sec. 3.3: variable sequence lengths are
+// Plan tables of the variable-length entry points (paper Sec. 3.3: variable sequence lengths are
 // served longest first, after a preprocessing kernel that sorts the batch).
 //
-// Input: cu_seqlens[0..B] (device), the running token count: sequence b owns token rows
-// cu[b] .. cu[b+1]-1.  Output: one int4 per 128-row tile, {first row of the sequence, its length,
-// tile index inside the sequence, 1}, sequences ordered by their tile count, longest first (a
-// counting sort: ties keep no particular order, which does not matter because no result depends
-// on which block computes which tile), and inside a sequence from the last tile to the first
-// (under a causal mask the last query tile has the longest key loop).  Unused entries up to
-// max_tiles are {0, 0, 0, 0}.  The kernels size their grids by max_tiles, a host-side upper
-// bound, because the host never reads cu_seqlens.
+// Input: cu_q[0..B] and cu_k[0..B] (device), the running token counts of the packed query-side
+// and key-side tensors: sequence b owns query rows cu_q[b] .. cu_q[b+1]-1 and key rows
+// cu_k[b] .. cu_k[b+1]-1 (cu_k may be the same array: self-attention).
+// Output: two tables, one entry per 128-row QUERY tile and one per 128-row KEY tile.  An entry is
+// two int4: {first query row, query length, first key row, key length} of the sequence and
+// {tile index inside the sequence, 1, 0, 0}.  Sequences are ordered by the length of the loop one
+// of their tiles runs -- the key tile count for query tiles, the query tile count for key tiles --
+// longest first (a counting sort over tile counts; ties keep no particular order, which does not
+// matter because no result depends on which block computes which tile), and inside a sequence
+// from the last tile to the first (under a causal mask the last query tile has the longest key
+// loop; the dK/dV kernels read the index backwards for the same reason).  Unused entries up to
+// the table size are zero.  The kernels size their grids by the table sizes, host-side upper
+// bounds, because the host never reads the lengths.
 #include "common.h"
 #include "launch.h"
 
 namespace attn {
 
 constexpr int PLAN_NT = 1024;
-constexpr int PLAN_BUCKETS = 4096;      // tile counts 0 .. 4095 (sequences up to 524 160 tokens); longer ones share the top bucket
+constexpr int PLAN_BUCKETS = 4096;      // loop lengths 0 .. 4095 tiles; longer ones share the top bucket
 
-__global__ void __launch_bounds__(PLAN_NT)
-varlen_plan_kernel(const int* __restrict__ cu, int B, int4* __restrict__ plan, int max_tiles)
+// One table.  own/other: the side whose tiles are listed and the side they loop over.
+__device__ void plan_build(const int* __restrict__ cu_q, const int* __restrict__ cu_k, int B, bool own_is_q,
+                           int4* __restrict__ plan, int max_tiles, int* hist, int* start, int* part)
 {
     static_assert(PLAN_BUCKETS == 4 * PLAN_NT, "four buckets per thread in the scan below");
-    __shared__ int hist[PLAN_BUCKETS];       // sequences per tile count, then next free slot per bucket
-    __shared__ int tile_start[PLAN_BUCKETS]; // first plan entry of each bucket
-    __shared__ int part[PLAN_NT];
     const int tid = threadIdx.x;
     for (int i = tid; i < PLAN_BUCKETS; i += PLAN_NT) hist[i] = 0;
-    for (int i = tid; i < max_tiles; i += PLAN_NT) plan[i] = make_int4(0, 0, 0, 0);
+    for (int i = tid; i < 2 * max_tiles; i += PLAN_NT) plan[i] = make_int4(0, 0, 0, 0);
     __syncthreads();
+    auto tiles = [](int len) { return (len + 127) / 128; };
+    auto bucket_of = [](int nt) { return nt < PLAN_BUCKETS ? nt : PLAN_BUCKETS - 1; };
+    // a sequence contributes its own tiles; query tiles of a sequence without keys are not listed
+    auto own_tiles = [&](int ql, int kl) { return own_is_q ? (kl > 0 ? tiles(ql) : 0) : tiles(kl); };
+    auto key_of = [&](int ql, int kl) { return bucket_of(tiles(own_is_q ? kl : ql)); };
 #ifdef ATTN_PLAN_GIVEN_ORDER   // measurement only: the batch order as given, no sort
     if (tid == 0) {
         int run = 0;
         for (int b = 0; b < B; ++b) {
-            const int len = cu[b + 1] - cu[b], nt = (len + 127) / 128;
-            for (int t = 0; t < nt && run < max_tiles; ++t) plan[run++] = make_int4(cu[b], len, nt - 1 - t, 1);
-        }
-    }
-    return;
-#endif
-    auto bucket_of = [](int nt) { return nt < PLAN_BUCKETS ? nt : PLAN_BUCKETS - 1; };
-    for (int b = tid; b < B; b += PLAN_NT) {
-        const int len = cu[b + 1] - cu[b];
-        if (len > 0) atomicAdd(&hist[bucket_of((len + 127) / 128)], 1);
-    }
-    __syncthreads();
-    // Sequences in the top bucket may differ in tile count, so that (normally empty) bucket is
-    // laid out first, by one thread, sequentially.
-    __shared__ int top_tiles;
-    if (tid == 0) {
-        int run = 0;
-        if (hist[PLAN_BUCKETS - 1] > 0) {
-            for (int b = 0; b < B; ++b) {
-                const int len = cu[b + 1] - cu[b];
-                const int nt = (len + 127) / 128;
-                if (len > 0 && nt >= PLAN_BUCKETS - 1)
-                    for (int t = 0; t < nt && run < max_tiles; ++t) plan[run++] = make_int4(cu[b], len, nt - 1 - t, 1);
+            const int qs = cu_q[b], ql = cu_q[b + 1] - qs, ks = cu_k[b], kl = cu_k[b + 1] - ks;
+            const int nt = own_tiles(ql, kl);
+            for (int t = 0; t < nt && run < max_tiles; ++t, ++run) {
+                plan[2 * run] = make_int4(qs, ql, ks, kl);
+                plan[2 * run + 1] = make_int4(nt - 1 - t, 1, 0, 0);
             }
         }
-        top_tiles = run;
     }
-    // Exclusive prefix sum of hist[nt] * nt over the other buckets from the largest tile count
-    // down.  Position p = 0 .. PLAN_BUCKETS-1 stands for bucket PLAN_BUCKETS-2-p (p beyond that: empty);
-    // every thread owns four consecutive positions.
-    auto weight = [&](int p) { const int nt = PLAN_BUCKETS - 2 - p; return nt >= 1 ? hist[nt] * nt : 0; };
+    __syncthreads();
+    return;
+#endif
+    for (int b = tid; b < B; b += PLAN_NT) {
+        const int ql = cu_q[b + 1] - cu_q[b], kl = cu_k[b + 1] - cu_k[b];
+        const int nt = own_tiles(ql, kl);
+        if (nt > 0) atomicAdd(&hist[key_of(ql, kl)], nt);
+    }
+    __syncthreads();
+    // Exclusive prefix sum of the tile counts over the buckets from the longest loop down.
+    // Position p = 0 .. PLAN_BUCKETS-1 stands for bucket PLAN_BUCKETS-1-p; every thread owns four
+    // consecutive positions.
     int w[4], local = 0;
 #pragma unroll
-    for (int e = 0; e < 4; ++e) { w[e] = weight(4 * tid + e); local += w[e]; }
+    for (int e = 0; e < 4; ++e) { w[e] = hist[PLAN_BUCKETS - 1 - (4 * tid + e)]; local += w[e]; }
     part[tid] = local;
     __syncthreads();
     for (int off = 1; off < PLAN_NT; off <<= 1) {          // inclusive Hillis-Steele scan of the partials
@@ -74,30 +71,46 @@ varlen_plan_kernel(const int* __restrict__ cu, int B, int4* __restrict__ plan, i
         part[tid] += add;
         __syncthreads();
     }
-    int run = top_tiles + part[tid] - local;
+    int run = part[tid] - local;
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
-        const int nt = PLAN_BUCKETS - 2 - (4 * tid + e);
-        if (nt >= 1) tile_start[nt] = run;
+        start[PLAN_BUCKETS - 1 - (4 * tid + e)] = run;
         run += w[e];
     }
     __syncthreads();
-    for (int i = tid; i < PLAN_BUCKETS - 1; i += PLAN_NT) hist[i] = 0;   // becomes the per-bucket sequence counter
+    for (int i = tid; i < PLAN_BUCKETS; i += PLAN_NT) hist[i] = 0;     // becomes the per-bucket tile cursor
     __syncthreads();
     for (int b = tid; b < B; b += PLAN_NT) {
-        const int start = cu[b], len = cu[b + 1] - start;
-        const int nt = (len + 127) / 128;
-        if (len <= 0 || nt >= PLAN_BUCKETS - 1) continue;
-        const int first = tile_start[nt] + atomicAdd(&hist[nt], 1) * nt;
+        const int qs = cu_q[b], ql = cu_q[b + 1] - qs, ks = cu_k[b], kl = cu_k[b + 1] - ks;
+        const int nt = own_tiles(ql, kl);
+        if (nt <= 0) continue;
+        const int key = key_of(ql, kl);
+        const int first = start[key] + atomicAdd(&hist[key], nt);
         for (int t = 0; t < nt; ++t)
-            if (first + t < max_tiles) plan[first + t] = make_int4(start, len, nt - 1 - t, 1);
+            if (first + t < max_tiles) {
+                plan[2 * (first + t)] = make_int4(qs, ql, ks, kl);
+                plan[2 * (first + t) + 1] = make_int4(nt - 1 - t, 1, 0, 0);
+            }
     }
+    __syncthreads();
 }
 
-int launch_varlen_plan(const int* cu_seqlens, int B, void* plan, int max_tiles, void* stream)
+__global__ void __launch_bounds__(PLAN_NT)
+varlen_plan_kernel(const int* __restrict__ cu_q, const int* __restrict__ cu_k, int B,
+                   int4* __restrict__ plan_q, int max_tiles_q, int4* __restrict__ plan_k, int max_tiles_k)
 {
-    return launch_kernel(varlen_plan_kernel, dim3(1), dim3(PLAN_NT), 0, stream, cu_seqlens, B, (int4*)plan,
-                         max_tiles) == hipSuccess ? 0 : -3;
+    __shared__ int hist[PLAN_BUCKETS];       // tiles per bucket, then next free tile per bucket
+    __shared__ int start[PLAN_BUCKETS];      // first table entry of each bucket
+    __shared__ int part[PLAN_NT];
+    plan_build(cu_q, cu_k, B, true, plan_q, max_tiles_q, hist, start, part);
+    if (plan_k) plan_build(cu_q, cu_k, B, false, plan_k, max_tiles_k, hist, start, part);   // backward only
+}
+
+int launch_varlen_plan(const int* cu_q, const int* cu_k, int B, void* plan_q, int max_tiles_q,
+                       void* plan_k, int max_tiles_k, void* stream)
+{
+    return launch_kernel(varlen_plan_kernel, dim3(1), dim3(PLAN_NT), 0, stream, cu_q, cu_k, B,
+                         (int4*)plan_q, max_tiles_q, (int4*)plan_k, max_tiles_k) == hipSuccess ? 0 : -3;
 }
 
 }  // namespace attn

@@ -14,8 +14,8 @@ struct FwdArgs {
     float scale;
     int causal;
     void* stream;
-    // variable-length mode (plan != nullptr): B and N unused, T = total tokens, max_tiles = size
-    // of the plan table (an upper bound on the number of 128-row tiles)
+    // variable-length mode (plan != nullptr): B and N unused; plan = table of query tiles,
+    // max_tiles its size (an upper bound on the number of 128-row query tiles), T = total query rows
     const void* plan = nullptr;
     int T = 0, max_tiles = 0;
     bool f16 = false;   // 16-bit storage type of q, k, v, o: bf16 (default) or IEEE fp16
@@ -33,8 +33,10 @@ struct BwdArgs {
     float* lse2;
     void* stream;
     int phases;   // bit mask: 1 prepare, 2 dK/dV kernel, 4 dQ kernel
-    const void* plan = nullptr;   // variable-length mode, as in FwdArgs
+    const void* plan = nullptr;   // variable-length mode, as in FwdArgs: query-tile table (dQ kernel)
     int T = 0, max_tiles = 0;
+    const void* plan_k = nullptr; // key-tile table (dK/dV kernels) and its size
+    int max_tiles_k = 0;
     bool f16 = false;             // as in FwdArgs
 };
 
@@ -72,7 +74,8 @@ struct LdsOptIn {
 // 0 on success, -2 unsupported head dims, -3 launch failure.
 int launch_fwd(const FwdArgs& a);
 int launch_bwd(const BwdArgs& a);
-// Fills the plan table of the variable-length entry points on the device: 0 or -3.
-int launch_varlen_plan(const int* cu_seqlens, int B, void* plan, int max_tiles, void* stream);
+// Fills the two plan tables of the variable-length entry points on the device: 0 or -3.
+int launch_varlen_plan(const int* cu_q, const int* cu_k, int B, void* plan_q, int max_tiles_q,
+                       void* plan_k, int max_tiles_k, void* stream);
 
 }  // namespace attn

@@ -99,23 +99,29 @@ def test_input_recipe_is_reproducible():
 
 def test_varlen_workspace_and_validation(L):
     import paper_2603_05451_amd as A
-    # plan table: (T/128 + B) entries of 16 bytes, rounded up to 256; backward adds -D and LSE2 [H, T]
-    fwd = A.attn_varlen_workspace_bytes(3, 1000, 4, 2, 128, 128, False)
-    bwd = A.attn_varlen_workspace_bytes(3, 1000, 4, 2, 128, 128, True)
-    assert fwd == 256 and bwd == 256 + 2 * 16128        # 10 entries -> 256; 4 * 1000 * 4 = 16000 -> 16128
-    assert A.attn_varlen_workspace_bytes(3, 1000, 3, 2, 128, 128, False) == 0      # H % Hkv != 0
-    assert A.attn_varlen_workspace_bytes(3, 1000, 4, 2, 96, 96, False) == 0        # unsupported head dim
-    assert A.attn_varlen_workspace_bytes(0, 1000, 4, 2, 64, 64, False) == 0
+    # tables: (T/128 + B) entries of 32 bytes per side, each rounded up to 256 (the forward call needs
+    # the query-tile table only); backward adds -D and LSE2 [H, Tq]
+    fwd = A.attn_varlen_workspace_bytes(3, 1000, 1000, 4, 2, 128, 128, False)
+    bwd = A.attn_varlen_workspace_bytes(3, 1000, 1000, 4, 2, 128, 128, True)
+    assert fwd == 512 and bwd == 512 + 512 + 2 * 16128  # 10 entries -> 320 -> 512; 4 * 1000 * 4 = 16000 -> 16128
+    bwd_x = A.attn_varlen_workspace_bytes(3, 1000, 5000, 4, 2, 128, 128, True)
+    assert bwd_x == 512 + 1536 + 2 * 16128              # 42 key-tile entries -> 1344 -> 1536; statistics sized by Tq
+    assert A.attn_varlen_workspace_bytes(3, 1000, 1000, 3, 2, 128, 128, False) == 0      # H % Hkv != 0
+    assert A.attn_varlen_workspace_bytes(3, 1000, 1000, 4, 2, 96, 96, False) == 0        # unsupported head dim
+    assert A.attn_varlen_workspace_bytes(0, 1000, 1000, 4, 2, 64, 64, False) == 0
+    assert A.attn_varlen_workspace_bytes(3, 1000, 0, 4, 2, 64, 64, False) == 0           # no keys at all
     p = ctypes.c_void_p(0x1000)
     w = ctypes.c_void_p(0x1000)
     call = lambda *a: L.attn_varlen_fwd(*a)
-    ok_tail = (3, 1000, 4, 2, 128, 128, 0.1, 0, w, 1 << 20, None)
-    assert call(None, p, p, p, p, p, *ok_tail) == A.ATTN_EINVAL
-    assert call(p, p, p, p, p, None, *ok_tail) == A.ATTN_EINVAL                    # cu_seqlens missing
-    assert call(p, p, p, p, p, p, 3, 1000, 4, 2, 128, 128, 0.1, 0, w, 16, None) == A.ATTN_EINVAL   # workspace too small
-    assert call(p, p, p, p, p, p, 3, 1000, 4, 2, 80, 80, 0.1, 0, w, 1 << 20, None) == A.ATTN_EUNSUPPORTED
-    assert call(p, p, p, p, p, p, 3, 1000, 4, 2, 128, 128, -1.0, 0, w, 1 << 20, None) == A.ATTN_EINVAL
-    assert L.attn_varlen_bwd(p, p, p, p, p, p, p, p, p, p, 3, 1000, 4, 2, 128, 128, 0.1, 0, w, 256, None) == A.ATTN_EINVAL
+    ok_tail = (3, 1000, 1000, 4, 2, 128, 128, 0.1, 0, w, 1 << 20, None)
+    assert call(None, p, p, p, p, p, p, *ok_tail) == A.ATTN_EINVAL
+    assert call(p, p, p, p, p, None, p, *ok_tail) == A.ATTN_EINVAL                 # cu_seqlens_q missing
+    assert call(p, p, p, p, p, p, None, *ok_tail) == A.ATTN_EINVAL                 # cu_seqlens_k missing
+    assert call(p, p, p, p, p, p, p, 3, 1000, 1000, 4, 2, 128, 128, 0.1, 0, w, 16, None) == A.ATTN_EINVAL   # workspace too small
+    assert call(p, p, p, p, p, p, p, 3, 1000, 1000, 4, 2, 80, 80, 0.1, 0, w, 1 << 20, None) == A.ATTN_EUNSUPPORTED
+    assert call(p, p, p, p, p, p, p, 3, 1000, 1000, 4, 2, 128, 128, -1.0, 0, w, 1 << 20, None) == A.ATTN_EINVAL
+    assert L.attn_varlen_bwd(p, p, p, p, p, p, p, p, p, p, p, 3, 1000, 1000, 4, 2, 128, 128, 0.1, 0, w, 256,
+                             None) == A.ATTN_EINVAL
 
 
 def test_varlen_workload_recipe_is_deterministic():

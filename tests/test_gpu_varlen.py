@@ -7,7 +7,7 @@ import pytest
 import torch
 
 from paper_2603_05451_amd import inputs as I
-from parity import LSE_ABS, assert_close
+from parity import LSE_ABS, assert_close, assert_close_wide
 
 pytestmark = pytest.mark.gpu
 
@@ -195,31 +195,147 @@ def test_varlen_many_short_sequences(oracle):
         assert ok(o[s][None], ro) and ok(dq[s][None], rdq) and ok(dk[s][None], rdk) and ok(dv[s][None], rdv)
 
 
-def test_plan_table_lists_every_tile_once_longest_first():
-    """The plan kernel's output (first section of the workspace): one entry per 128-row tile of every
-    non-empty sequence, sequences with more tiles before sequences with fewer, a sequence's tiles
-    contiguous and from last to first, the rest of the table marked unused."""
+def read_tables(ws, B, Tq, Tk):
+    """The two tile tables at the head of a backward workspace, as int arrays [entries, 8]:
+    {first query row, query length, first key row, key length, tile, valid, 0, 0}."""
+    mq, mk = Tq // 128 + B, Tk // 128 + B
+    off_k = (mq * 32 + 255) // 256 * 256
+    tq = ws[:mq * 32].view(torch.int32).reshape(mq, 8).cpu().numpy()
+    tk = ws[off_k:off_k + mk * 32].view(torch.int32).reshape(mk, 8).cpu().numpy()
+    return tq, tk
+
+
+def check_table(table, want, loop_tiles):
+    """want: set of (q start, q len, k start, k len, tile); loop_tiles(entry) = length of the loop a
+    tile of that sequence runs.  Every wanted tile once, longest loops first, a sequence's tiles
+    contiguous and from last to first, the rest of the table zero."""
+    used = table[table[:, 5] == 1]
+    assert len(used) == len(want) and {tuple(int(x) for x in e[:5]) for e in used} == want
+    assert (table[len(used):] == 0).all() and (used[:, 6:] == 0).all()
+    loops = np.array([loop_tiles(e) for e in used])
+    assert (np.diff(loops) <= 0).all()
+    seen, i = set(), 0
+    while i < len(used):
+        key = tuple(int(x) for x in used[i, :4])
+        assert key not in seen
+        seen.add(key)
+        nt = int(used[i, 4]) + 1                                # a run starts at the sequence's last tile
+        assert (used[i:i + nt, :4] == used[i, :4]).all() and list(used[i:i + nt, 4]) == list(range(nt - 1, -1, -1))
+        i += nt
+
+
+def test_plan_tables_list_every_tile_once_longest_first():
+    """The plan kernel's output (head of the workspace): one entry per 128-row query tile (sequences
+    with keys) and per 128-row key tile, ordered by the number of tiles of the OTHER side, which is
+    the loop a tile runs."""
     import paper_2603_05451_amd as A
     rng = np.random.default_rng(3)
-    lengths = [int(n) for n in np.concatenate([rng.integers(0, 700, 300), [0, 1, 128, 129, 4096, 5000]])]
-    rng.shuffle(lengths)
-    cu = np.concatenate([[0], np.cumsum(lengths)]).astype(np.int32)
-    T, B, H, d = int(cu[-1]), len(lengths), 1, 64
-    q = torch.zeros(T, H, d, dtype=torch.bfloat16, device="cuda")
-    ws = torch.empty(A.attn_varlen_workspace_bytes(B, T, H, H, d, d, False), dtype=torch.uint8, device="cuda")
-    A.attn_varlen_fwd(q, q, q, torch.from_numpy(cu).cuda(), 0.125, False, workspace=ws)
+    ql = [int(n) for n in np.concatenate([rng.integers(0, 700, 300), [0, 1, 128, 129, 4096, 5000, 7, 0]])]
+    kl = [int(n) for n in np.concatenate([rng.integers(1, 900, 300), [5, 1, 128, 300, 4096, 5000, 0, 0]])]
+    perm = rng.permutation(len(ql))
+    ql, kl = [ql[i] for i in perm], [kl[i] for i in perm]
+    cuq = np.concatenate([[0], np.cumsum(ql)]).astype(np.int32)
+    cuk = np.concatenate([[0], np.cumsum(kl)]).astype(np.int32)
+    Tq, Tk, B, H, d = int(cuq[-1]), int(cuk[-1]), len(ql), 1, 64
+    # sequences without keys get no query tiles, so the (undefined) rows are simply not touched;
+    # keep the kernels away from them anyway: this test runs the backward of zeros
+    z = lambda T: torch.zeros(T, H, d, dtype=torch.bfloat16, device="cuda")
+    ws = torch.empty(A.attn_varlen_workspace_bytes(B, Tq, Tk, H, H, d, d, True), dtype=torch.uint8, device="cuda")
+    lse = torch.zeros(H, Tq, dtype=torch.float32, device="cuda")
+    A.attn_varlen_bwd(z(Tq), z(Tk), z(Tk), z(Tq), z(Tq), lse, torch.from_numpy(cuq).cuda(), 0.125, False,
+                      workspace=ws, cu_seqlens_k=torch.from_numpy(cuk).cuda())
     torch.cuda.synchronize()
-    max_tiles = T // 128 + B
-    plan = ws[:max_tiles * 16].view(torch.int32).reshape(max_tiles, 4).cpu().numpy()
-    want = {(int(cu[b]), n, t) for b, n in enumerate(lengths) for t in range((n + 127) // 128)}
-    used = plan[plan[:, 3] == 1]
-    assert len(used) == len(want) and {tuple(int(x) for x in e[:3]) for e in used} == want
-    assert (plan[len(used):] == 0).all()                                  # valid entries first, then zeros
-    tiles_of = (used[:, 1] + 127) // 128
-    assert (np.diff(tiles_of) <= 0).all()                                 # most tiles first
-    i = 0
-    while i < len(used):                                                  # runs: one sequence, tiles nt-1 .. 0
-        nt = int(tiles_of[i])
-        run = used[i:i + nt]
-        assert (run[:, 0] == run[0, 0]).all() and list(run[:, 2]) == list(range(nt - 1, -1, -1))
-        i += nt
+    tq, tk = read_tables(ws, B, Tq, Tk)
+    tiles = lambda n: (n + 127) // 128
+    seqs = [(int(cuq[b]), ql[b], int(cuk[b]), kl[b]) for b in range(B)]
+    check_table(tq, {(*e, t) for e in seqs if e[3] > 0 for t in range(tiles(e[1]))}, lambda e: tiles(int(e[3])))
+    check_table(tk, {(*e, t) for e in seqs for t in range(tiles(e[3]))}, lambda e: tiles(int(e[1])))
+
+
+def cross_inputs(qlens, klens, H, Hkv, dqk, dv, seed):
+    """Packed tensors with separate query and key row counts, from the N(0,1) recipe."""
+    Tq, Tk = int(sum(qlens)), int(sum(klens))
+    w = I.Workload("cross", 1, H, Hkv, max(Tq, Tk), dqk, dv, False, seed)
+    x = I.make_inputs(w, with_do=True)
+    out = {n: x[n][0, :(Tq if n in ("q", "do") else Tk)].contiguous() for n in ("q", "k", "v", "do")}
+    cuq = np.concatenate([[0], np.cumsum(qlens)]).astype(np.int32)
+    cuk = np.concatenate([[0], np.cumsum(klens)]).astype(np.int32)
+    return out, cuq, cuk, w.scale
+
+
+# (queries, keys) per sequence.  Non-causal: any combination, also more queries than keys and a
+# sequence without queries.  Causal: keys >= queries (the last query sees every key): one decoded
+# token against a long cache, a chunk appended to a prefix whose length is not a multiple of any
+# tile size, equal lengths.
+CROSS_NC = ([1, 200, 64, 129, 0, 700, 128, 333], [1000, 64, 200, 129, 300, 1, 640, 77])
+CROSS_C = ([1, 1, 64, 129, 0, 100, 128, 333, 5], [1000, 1, 200, 129, 300, 611, 640, 333, 130])
+CROSS_CASES = [
+    ("d64_nc", CROSS_NC, 4, 2, 64, 64, False, 61),
+    ("d64_c", CROSS_C, 2, 1, 64, 64, True, 62),
+    ("d128_nc", CROSS_NC, 4, 2, 128, 128, False, 63),
+    ("d128_c", CROSS_C, 4, 1, 128, 128, True, 64),
+    ("d192_nc", CROSS_NC, 2, 2, 192, 128, False, 65),
+    ("d192_c", CROSS_C, 2, 1, 192, 128, True, 66),
+]
+
+
+@pytest.mark.parametrize("name,lens,H,Hkv,dqk,dv,causal,seed", CROSS_CASES, ids=[c[0] for c in CROSS_CASES])
+def test_varlen_separate_query_and_key_lengths(oracle, name, lens, H, Hkv, dqk, dv, causal, seed):
+    """Query and key counts differ per sequence; under the causal mask the last query is aligned
+    with the last key, which the oracle expresses through the query positions."""
+    import paper_2603_05451_amd as A
+    qlens, klens = lens
+    x, cuq, cuk, scale = cross_inputs(qlens, klens, H, Hkv, dqk, dv, seed)
+    q, k, v, do = (x[n].cuda() for n in ("q", "k", "v", "do"))
+    cuqd, cukd = torch.from_numpy(cuq).cuda(), torch.from_numpy(cuk).cuda()
+    nan = lambda t: torch.full_like(t, float("nan"))
+    o = torch.full((q.shape[0], H, dv), float("nan"), dtype=torch.bfloat16, device="cuda")
+    o, lse = A.attn_varlen_fwd(q, k, v, cuqd, scale, causal, o=o, cu_seqlens_k=cukd)
+    dq, dk, dvv = A.attn_varlen_bwd(q, k, v, o, do, lse, cuqd, scale, causal, dq=nan(q), dk=nan(k), dv=nan(v),
+                                    cu_seqlens_k=cukd)
+    torch.cuda.synchronize()
+    o, lse, dq, dk, dvv = (t.float().cpu().numpy() for t in (o, lse, dq, dk, dvv))
+    assert all(np.isfinite(t).all() for t in (o, lse, dq, dk, dvv))            # every row written
+    wide = lambda got, ref: (np.abs(got - ref) <= 2e-2 + 2.0 ** -8 * np.abs(ref)).all()
+    for b, (nq, nk) in enumerate(zip(qlens, klens)):
+        sq, sk = slice(int(cuq[b]), int(cuq[b + 1])), slice(int(cuk[b]), int(cuk[b + 1]))
+        if nq == 0:
+            assert (dk[sk] == 0).all() and (dvv[sk] == 0).all()                 # keys nobody attends to
+            continue
+        pos = np.arange(nq) + (nk - nq)
+        fq, fk, fv, fdo = (I.to_f64(x[m][s][None]) for m, s in (("q", sq), ("k", sk), ("v", sk), ("do", sq)))
+        ro, rlse = oracle.attn_fwd(fq, fk, fv, scale, causal, q_pos=pos)
+        rdq, rdk, rdv = oracle.attn_bwd(fq, fk, fv, fdo, scale, causal, q_pos=pos)
+        tag = f"{name} seq{b} q{nq} k{nk}"
+        assert np.abs(lse[:, sq][None] - rlse).max() <= LSE_ABS, tag
+        if min(nq, nk) < 32:
+            # a handful of queries or keys: peaked softmaxes, outputs of magnitude > 4, reference
+            # rows that are exactly zero -> absolute bound plus the output-rounding term
+            assert wide(o[sq][None], ro) and wide(dq[sq][None], rdq) and wide(dk[sk][None], rdk) and \
+                wide(dvv[sk][None], rdv), tag
+            continue
+        assert_close(o[sq][None], ro, "O " + tag)
+        assert_close(dq[sq][None], rdq, "dQ " + tag)
+        # dK / dV summed over the query heads of a group exceed magnitude 4 on the first keys of a
+        # causal sequence: the output-rounding term joins the absolute bound there
+        close_kv = assert_close_wide if H != Hkv else assert_close
+        close_kv(dk[sk][None], rdk, "dK " + tag)
+        close_kv(dvv[sk][None], rdv, "dV " + tag)
+
+
+def test_varlen_decode_step_matches_last_row_of_prefill():
+    """Causal attention of the last token against the whole sequence (1 query, N keys) is row N-1 of
+    causal self-attention: same keys, same mask row; the tiles are cut differently, so the match is
+    to rounding, not bitwise."""
+    import paper_2603_05451_amd as A
+    lengths = [300, 1025, 64, 4097]
+    x, cu, scale = packed_inputs(lengths, 4, 2, 128, 128, 71)
+    q, k, v = (x[n].cuda() for n in ("q", "k", "v"))
+    cud = torch.from_numpy(cu).cuda()
+    o_full, lse_full = A.attn_varlen_fwd(q, k, v, cud, scale, True)
+    last = torch.from_numpy(cu[1:] - 1).long().cuda()
+    cu1 = torch.arange(0, len(lengths) + 1, dtype=torch.int32, device="cuda")
+    o_dec, lse_dec = A.attn_varlen_fwd(q[last].contiguous(), k, v, cu1, scale, True, cu_seqlens_k=cud)
+    torch.cuda.synchronize()
+    assert (o_dec.float() - o_full[last].float()).abs().max().item() <= 2e-2
+    assert (lse_dec - lse_full[:, last]).abs().max().item() <= 2 * LSE_ABS
