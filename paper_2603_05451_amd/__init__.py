@@ -57,6 +57,13 @@ def lib():
         L.attn_varlen_bwd_dtype.restype = i
         L.attn_varlen_workspace_bytes.argtypes = [i] * 8
         L.attn_varlen_workspace_bytes.restype = sz
+        sp = ctypes.POINTER(AttnStrides)
+        L.attn_strided_workspace_bytes.argtypes = [i] * 7
+        L.attn_strided_workspace_bytes.restype = sz
+        L.attn_fwd_strided.argtypes = [i] + [vp, sp] * 4 + [vp] + [i] * 6 + [f, i, vp, sz, vp]
+        L.attn_fwd_strided.restype = i
+        L.attn_bwd_strided.argtypes = [i] + [vp, sp] * 5 + [vp] + [vp, sp] * 3 + [i] * 6 + [f, i, vp, sz, vp]
+        L.attn_bwd_strided.restype = i
         L.attn_varlen_fwd.argtypes = [vp] * 7 + [i] * 7 + [f, i, vp, sz, vp]
         L.attn_varlen_fwd.restype = i
         L.attn_varlen_bwd.argtypes = [vp] * 11 + [i] * 7 + [f, i, vp, sz, vp]
@@ -212,6 +219,74 @@ def attn_varlen_bwd(q, k, v, o, d_o, lse, cu_seqlens, scale, causal, dq=None, dk
             float(scale), int(bool(causal)),
             ctypes.c_void_p(workspace.data_ptr()), workspace.numel(), _stream(stream))
     rc = lib().attn_varlen_bwd(*args) if code == ATTN_BF16 else lib().attn_varlen_bwd_dtype(code, *args)
+    _check(rc)
+    return dq, dk, dv
+
+
+class AttnStrides(ctypes.Structure):
+    """attn_strides_t of include/attn.h: element strides of the batch, token and head axes."""
+    _fields_ = [("batch", ctypes.c_longlong), ("row", ctypes.c_longlong), ("head", ctypes.c_longlong)]
+
+
+def _view(t, name, shape, like):
+    """(pointer, strides) of a [B, N, heads, d] view with a contiguous head dim."""
+    if not (t.is_cuda and t.dtype == like.dtype and t.dim() == 4 and (t.stride(3) == 1 or t.shape[3] == 1)):
+        raise ValueError(f"{name} must be a 4-d {like.dtype} CUDA tensor with a contiguous last axis")
+    if tuple(t.shape) != tuple(shape):
+        raise ValueError(f"{name} has shape {tuple(t.shape)}, expected {tuple(shape)}")
+    return ctypes.c_void_p(t.data_ptr()), ctypes.byref(AttnStrides(t.stride(0), t.stride(1), t.stride(2)))
+
+
+def attn_strided_workspace_bytes(B, H, Hkv, N, d_qk, d_v, backward) -> int:
+    return int(lib().attn_strided_workspace_bytes(B, H, Hkv, N, d_qk, d_v, int(bool(backward))))
+
+
+def attn_fwd_strided(q, k, v, scale, causal, o=None, lse=None, workspace=None, stream=None):
+    """attn_fwd on views: q [B,N,H,d_qk], k [B,N,Hkv,d_qk], v [B,N,Hkv,d_v] of any strides (the last
+    axis contiguous), e.g. x.permute(0, 2, 1, 3) of a [B,H,N,d] tensor; any N >= 1.  o may be a view
+    too (default: a new contiguous [B,N,H,d_v]); lse [B,H,N] fp32 contiguous."""
+    import torch
+    B, N, H, dqk = q.shape
+    Hkv, dv = k.shape[2], v.shape[3]
+    if o is None:
+        o = torch.empty((B, N, H, dv), dtype=q.dtype, device=q.device)
+    if lse is None:
+        lse = torch.empty((B, H, N), dtype=torch.float32, device=q.device)
+    if not (lse.is_cuda and lse.dtype == torch.float32 and lse.is_contiguous() and tuple(lse.shape) == (B, H, N)):
+        raise ValueError("lse must be a contiguous fp32 CUDA tensor [B,H,N]")
+    need = attn_strided_workspace_bytes(B, H, Hkv, N, dqk, dv, False)
+    if workspace is None:
+        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=q.device)
+    rc = lib().attn_fwd_strided(_dtype_code(q), *_view(q, "q", (B, N, H, dqk), q), *_view(k, "k", (B, N, Hkv, dqk), q),
+                                *_view(v, "v", (B, N, Hkv, dv), q), *_view(o, "o", (B, N, H, dv), q),
+                                ctypes.c_void_p(lse.data_ptr()), B, H, Hkv, N, dqk, dv, float(scale),
+                                int(bool(causal)), ctypes.c_void_p(workspace.data_ptr()), workspace.numel(),
+                                _stream(stream))
+    _check(rc)
+    return o, lse
+
+
+def attn_bwd_strided(q, k, v, o, d_o, lse, scale, causal, dq=None, dk=None, dv=None, workspace=None, stream=None):
+    """Backward of attn_fwd_strided; every tensor may be a view.  Gradients default to new
+    contiguous [B,N,heads,d] tensors."""
+    import torch
+    B, N, H, dqk = q.shape
+    Hkv, dv_ = k.shape[2], v.shape[3]
+    dq = torch.empty((B, N, H, dqk), dtype=q.dtype, device=q.device) if dq is None else dq
+    dk = torch.empty((B, N, Hkv, dqk), dtype=q.dtype, device=q.device) if dk is None else dk
+    dv = torch.empty((B, N, Hkv, dv_), dtype=q.dtype, device=q.device) if dv is None else dv
+    if not (lse.is_cuda and lse.dtype == torch.float32 and lse.is_contiguous() and tuple(lse.shape) == (B, H, N)):
+        raise ValueError("lse must be a contiguous fp32 CUDA tensor [B,H,N]")
+    need = attn_strided_workspace_bytes(B, H, Hkv, N, dqk, dv_, True)
+    if workspace is None:
+        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=q.device)
+    rc = lib().attn_bwd_strided(_dtype_code(q), *_view(q, "q", (B, N, H, dqk), q), *_view(k, "k", (B, N, Hkv, dqk), q),
+                                *_view(v, "v", (B, N, Hkv, dv_), q), *_view(o, "o", (B, N, H, dv_), q),
+                                *_view(d_o, "d_o", (B, N, H, dv_), q), ctypes.c_void_p(lse.data_ptr()),
+                                *_view(dq, "dq", (B, N, H, dqk), q), *_view(dk, "dk", (B, N, Hkv, dqk), q),
+                                *_view(dv, "dv", (B, N, Hkv, dv_), q), B, H, Hkv, N, dqk, dv_, float(scale),
+                                int(bool(causal)), ctypes.c_void_p(workspace.data_ptr()), workspace.numel(),
+                                _stream(stream))
     _check(rc)
     return dq, dk, dv
 

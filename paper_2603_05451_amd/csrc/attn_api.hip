@@ -181,6 +181,60 @@ VarlenLayout varlen_layout(int B, int Tq, int Tk, int H)
     return w;
 }
 
+// Strides of packed [T, heads, d] tensors and of lse [H, Tq].
+attn::VarlenStrides packed_strides(int Tq, int H, int Hkv, int d_qk, int d_v)
+{
+    attn::VarlenStrides st;
+    st.q = st.dq = {0, (long long)H * d_qk, d_qk};
+    st.k = st.dk = {0, (long long)Hkv * d_qk, d_qk};
+    st.v = st.dv = {0, (long long)Hkv * d_v, d_v};
+    st.o = st.d_o = {0, (long long)H * d_v, d_v};
+    st.lse_batch = 0;
+    st.lse_head = Tq;
+    return st;
+}
+
+int varlen_fwd_run(int dtype, const void* q, const void* k, const void* v, void* o, float* lse,
+                   const int* cu_q, const int* cu_k, int B, int Tq, int Tk, int H, int Hkv, int d_qk, int d_v,
+                   float scale, int causal, char* ws, const attn::VarlenStrides& st, void* stream)
+{
+    const VarlenLayout w = varlen_layout(B, Tq, Tk, H);
+    if (attn::launch_varlen_plan(cu_q, cu_k, B, ws + w.plan_q_off, w.max_tiles_q, nullptr, 0, stream) != 0)
+        return ATTN_ELAUNCH;
+    attn::FwdArgs a{q, k, v, o, lse, B, H, Hkv, 0, d_qk, d_v, scale, causal != 0, stream};
+    a.plan = ws + w.plan_q_off;
+    a.T = Tq;
+    a.max_tiles = w.max_tiles_q;
+    a.st = st;
+    a.f16 = dtype == ATTN_F16;
+    const int rc = attn::launch_fwd(a);
+    return rc == 0 ? ATTN_OK : (rc == -2 ? ATTN_EUNSUPPORTED : ATTN_ELAUNCH);
+}
+
+int varlen_bwd_run(int dtype, const void* q, const void* k, const void* v, const void* o, const void* d_o,
+                   const float* lse, void* dq, void* dk, void* dv,
+                   const int* cu_q, const int* cu_k, int B, int Tq, int Tk, int H, int Hkv, int d_qk, int d_v,
+                   float scale, int causal, char* ws, const attn::VarlenStrides& st, int rows_per_batch, void* stream)
+{
+    const VarlenLayout w = varlen_layout(B, Tq, Tk, H);
+    if (attn::launch_varlen_plan(cu_q, cu_k, B, ws + w.plan_q_off, w.max_tiles_q,
+                                 ws + w.plan_k_off, w.max_tiles_k, stream) != 0)
+        return ATTN_ELAUNCH;
+    attn::BwdArgs a{q, k, v, o, d_o, lse, dq, dk, dv, B, H, Hkv, 0, d_qk, d_v, scale, causal != 0,
+                    reinterpret_cast<float*>(ws + w.d_off), reinterpret_cast<float*>(ws + w.lse2_off),
+                    stream, ATTN_BWD_ALL};
+    a.plan = ws + w.plan_q_off;
+    a.T = Tq;
+    a.max_tiles = w.max_tiles_q;
+    a.plan_k = ws + w.plan_k_off;
+    a.max_tiles_k = w.max_tiles_k;
+    a.st = st;
+    a.rows_per_batch = rows_per_batch;
+    a.f16 = dtype == ATTN_F16;
+    const int rc = attn::launch_bwd(a);
+    return rc == 0 ? ATTN_OK : (rc == -2 ? ATTN_EUNSUPPORTED : ATTN_ELAUNCH);
+}
+
 }  // namespace
 
 size_t attn_varlen_workspace_bytes(int B, int total_q, int total_k, int H, int Hkv, int d_qk, int d_v, int backward)
@@ -202,18 +256,10 @@ int attn_varlen_fwd_dtype(int dtype, const void* q, const void* k, const void* v
     if (misaligned(q, 16) || misaligned(k, 16) || misaligned(v, 16) || misaligned(o, 16) ||
         misaligned(lse, 4) || misaligned(cu_seqlens_q, 4) || misaligned(cu_seqlens_k, 4) || misaligned(workspace, 256))
         return ATTN_EINVAL;
-    const VarlenLayout w = varlen_layout(B, total_q, total_k, H);
-    if (workspace_bytes < w.total_fwd) return ATTN_EINVAL;
-    char* ws = static_cast<char*>(workspace);
-    if (attn::launch_varlen_plan(cu_seqlens_q, cu_seqlens_k, B, ws + w.plan_q_off, w.max_tiles_q, nullptr, 0, stream) != 0)
-        return ATTN_ELAUNCH;
-    attn::FwdArgs a{q, k, v, o, lse, B, H, Hkv, 0, d_qk, d_v, scale, causal != 0, stream};
-    a.plan = ws + w.plan_q_off;
-    a.T = total_q;
-    a.max_tiles = w.max_tiles_q;
-    a.f16 = dtype == ATTN_F16;
-    const int rc = attn::launch_fwd(a);
-    return rc == 0 ? ATTN_OK : (rc == -2 ? ATTN_EUNSUPPORTED : ATTN_ELAUNCH);
+    if (workspace_bytes < varlen_layout(B, total_q, total_k, H).total_fwd) return ATTN_EINVAL;
+    return varlen_fwd_run(dtype, q, k, v, o, lse, cu_seqlens_q, cu_seqlens_k, B, total_q, total_k, H, Hkv, d_qk, d_v,
+                          scale, causal, static_cast<char*>(workspace), packed_strides(total_q, H, Hkv, d_qk, d_v),
+                          stream);
 }
 
 int attn_varlen_fwd(const void* q, const void* k, const void* v, void* o, float* lse,
@@ -241,23 +287,10 @@ int attn_varlen_bwd_dtype(int dtype, const void* q, const void* k, const void* v
         if (misaligned(p, 16)) return ATTN_EINVAL;
     if (misaligned(lse, 4) || misaligned(cu_seqlens_q, 4) || misaligned(cu_seqlens_k, 4) || misaligned(workspace, 256))
         return ATTN_EINVAL;
-    const VarlenLayout w = varlen_layout(B, total_q, total_k, H);
-    if (workspace_bytes < w.total_bwd) return ATTN_EINVAL;
-    char* ws = static_cast<char*>(workspace);
-    if (attn::launch_varlen_plan(cu_seqlens_q, cu_seqlens_k, B, ws + w.plan_q_off, w.max_tiles_q,
-                                 ws + w.plan_k_off, w.max_tiles_k, stream) != 0)
-        return ATTN_ELAUNCH;
-    attn::BwdArgs a{q, k, v, o, d_o, lse, dq, dk, dv, B, H, Hkv, 0, d_qk, d_v, scale, causal != 0,
-                    reinterpret_cast<float*>(ws + w.d_off), reinterpret_cast<float*>(ws + w.lse2_off),
-                    stream, ATTN_BWD_ALL};
-    a.plan = ws + w.plan_q_off;
-    a.T = total_q;
-    a.max_tiles = w.max_tiles_q;
-    a.plan_k = ws + w.plan_k_off;
-    a.max_tiles_k = w.max_tiles_k;
-    a.f16 = dtype == ATTN_F16;
-    const int rc = attn::launch_bwd(a);
-    return rc == 0 ? ATTN_OK : (rc == -2 ? ATTN_EUNSUPPORTED : ATTN_ELAUNCH);
+    if (workspace_bytes < varlen_layout(B, total_q, total_k, H).total_bwd) return ATTN_EINVAL;
+    return varlen_bwd_run(dtype, q, k, v, o, d_o, lse, dq, dk, dv, cu_seqlens_q, cu_seqlens_k, B, total_q, total_k,
+                          H, Hkv, d_qk, d_v, scale, causal, static_cast<char*>(workspace),
+                          packed_strides(total_q, H, Hkv, d_qk, d_v), 0, stream);
 }
 
 int attn_varlen_bwd(const void* q, const void* k, const void* v, const void* o, const void* d_o,
@@ -269,6 +302,114 @@ int attn_varlen_bwd(const void* q, const void* k, const void* v, const void* o, 
     return attn_varlen_bwd_dtype(ATTN_BF16, q, k, v, o, d_o, lse, dq, dk, dv, cu_seqlens_q, cu_seqlens_k, B,
                                  total_q, total_k, H, Hkv, d_qk, d_v, scale, causal, workspace, workspace_bytes,
                                  stream);
+}
+
+// ---------------------------------------------------------------------------------------------
+// strided entry points: equal-length batches in any layout whose head dim is contiguous, run by
+// the variable-length kernels on a generated cu_seqlens = {0, N, 2N, ...}
+
+namespace {
+
+size_t cu_bytes(int B) { return align_up((size_t)(B + 1) * sizeof(int), 256); }
+
+int check_strided(int B, int H, int Hkv, int N, int d_qk, int d_v)
+{
+    if (B <= 0 || N <= 0) return ATTN_EINVAL;
+    if ((int64_t)B * N > 0x7fffffffLL) return ATTN_EUNSUPPORTED;
+    return check_varlen(B, B * N, B * N, H, Hkv, d_qk, d_v);
+}
+
+// every stride a multiple of 8 elements (16 bytes: vector loads and the global->LDS copies),
+// rows and heads apart (stride 0 only where there is a single one)
+bool bad_stride(const attn_strides_t* s, int B, int N, int heads)
+{
+    if (!s) return true;
+    if (s->batch % 8 || s->row % 8 || s->head % 8) return true;
+    if (s->batch < 0 || s->row < 0 || s->head < 0) return true;
+    if ((B > 1 && s->batch == 0) || (N > 1 && s->row == 0) || (heads > 1 && s->head == 0)) return true;
+    if (s->row > (1LL << 23)) return true;     // byte offsets inside a 128-row tile are 32-bit
+    return false;
+}
+
+attn::Stride3 as_packed(const attn_strides_t* s, int N)
+{
+    return {s->batch - (long long)N * s->row, s->row, s->head};
+}
+
+}  // namespace
+
+size_t attn_strided_workspace_bytes(int B, int H, int Hkv, int N, int d_qk, int d_v, int backward)
+{
+    if (check_strided(B, H, Hkv, N, d_qk, d_v) != ATTN_OK) return 0;
+    const VarlenLayout w = varlen_layout(B, B * N, B * N, H);
+    return cu_bytes(B) + (backward ? w.total_bwd : w.total_fwd);
+}
+
+int attn_fwd_strided(int dtype, const void* q, const attn_strides_t* sq, const void* k, const attn_strides_t* sk,
+                     const void* v, const attn_strides_t* sv, void* o, const attn_strides_t* so, float* lse,
+                     int B, int H, int Hkv, int N, int d_qk, int d_v, float scale, int causal,
+                     void* workspace, size_t workspace_bytes, void* stream)
+{
+    if (dtype != ATTN_BF16 && dtype != ATTN_F16) return ATTN_EUNSUPPORTED;
+    if (!q || !k || !v || !o || !lse || !workspace) return ATTN_EINVAL;
+    if (int rc = check_strided(B, H, Hkv, N, d_qk, d_v)) return rc;
+    if (bad_stride(sq, B, N, H) || bad_stride(sk, B, N, Hkv) || bad_stride(sv, B, N, Hkv) || bad_stride(so, B, N, H))
+        return ATTN_EINVAL;
+    if (!(scale > 0.0f) || !(scale < 1e30f)) return ATTN_EINVAL;
+    if (misaligned(q, 16) || misaligned(k, 16) || misaligned(v, 16) || misaligned(o, 16) ||
+        misaligned(lse, 4) || misaligned(workspace, 256))
+        return ATTN_EINVAL;
+    if (workspace_bytes < attn_strided_workspace_bytes(B, H, Hkv, N, d_qk, d_v, 0)) return ATTN_EINVAL;
+    char* ws = static_cast<char*>(workspace);
+    int* cu = reinterpret_cast<int*>(ws);
+    if (attn::launch_uniform_cu(cu, B, N, stream) != 0) return ATTN_ELAUNCH;
+    attn::VarlenStrides st = {};
+    st.q = as_packed(sq, N);
+    st.k = as_packed(sk, N);
+    st.v = as_packed(sv, N);
+    st.o = as_packed(so, N);
+    st.lse_head = N;                       // lse [B, H, N]
+    st.lse_batch = (long long)(H - 1) * N;
+    return varlen_fwd_run(dtype, q, k, v, o, lse, cu, cu, B, B * N, B * N, H, Hkv, d_qk, d_v, scale, causal,
+                          ws + cu_bytes(B), st, stream);
+}
+
+int attn_bwd_strided(int dtype, const void* q, const attn_strides_t* sq, const void* k, const attn_strides_t* sk,
+                     const void* v, const attn_strides_t* sv, const void* o, const attn_strides_t* so,
+                     const void* d_o, const attn_strides_t* sdo, const float* lse,
+                     void* dq, const attn_strides_t* sdq, void* dk, const attn_strides_t* sdk,
+                     void* dv, const attn_strides_t* sdv,
+                     int B, int H, int Hkv, int N, int d_qk, int d_v, float scale, int causal,
+                     void* workspace, size_t workspace_bytes, void* stream)
+{
+    if (dtype != ATTN_BF16 && dtype != ATTN_F16) return ATTN_EUNSUPPORTED;
+    if (!q || !k || !v || !o || !d_o || !lse || !dq || !dk || !dv || !workspace) return ATTN_EINVAL;
+    if (int rc = check_strided(B, H, Hkv, N, d_qk, d_v)) return rc;
+    if (bad_stride(sq, B, N, H) || bad_stride(sk, B, N, Hkv) || bad_stride(sv, B, N, Hkv) || bad_stride(so, B, N, H) ||
+        bad_stride(sdo, B, N, H) || bad_stride(sdq, B, N, H) || bad_stride(sdk, B, N, Hkv) || bad_stride(sdv, B, N, Hkv))
+        return ATTN_EINVAL;
+    if (!(scale > 0.0f) || !(scale < 1e30f)) return ATTN_EINVAL;
+    const void* ptrs[] = {q, k, v, o, d_o, dq, dk, dv};
+    for (const void* p : ptrs)
+        if (misaligned(p, 16)) return ATTN_EINVAL;
+    if (misaligned(lse, 4) || misaligned(workspace, 256)) return ATTN_EINVAL;
+    if (workspace_bytes < attn_strided_workspace_bytes(B, H, Hkv, N, d_qk, d_v, 1)) return ATTN_EINVAL;
+    char* ws = static_cast<char*>(workspace);
+    int* cu = reinterpret_cast<int*>(ws);
+    if (attn::launch_uniform_cu(cu, B, N, stream) != 0) return ATTN_ELAUNCH;
+    attn::VarlenStrides st = {};
+    st.q = as_packed(sq, N);
+    st.k = as_packed(sk, N);
+    st.v = as_packed(sv, N);
+    st.o = as_packed(so, N);
+    st.d_o = as_packed(sdo, N);
+    st.dq = as_packed(sdq, N);
+    st.dk = as_packed(sdk, N);
+    st.dv = as_packed(sdv, N);
+    st.lse_head = N;
+    st.lse_batch = (long long)(H - 1) * N;
+    return varlen_bwd_run(dtype, q, k, v, o, d_o, lse, dq, dk, dv, cu, cu, B, B * N, B * N, H, Hkv, d_qk, d_v,
+                          scale, causal, ws + cu_bytes(B), st, N, stream);
 }
 
 const char* attn_strerror(int code)

@@ -6,7 +6,7 @@
 // cu_k[b] .. cu_k[b+1]-1 (cu_k may be the same array: self-attention).
 // Output: two tables, one entry per 128-row QUERY tile and one per 128-row KEY tile.  An entry is
 // two int4: {first query row, query length, first key row, key length} of the sequence and
-// {tile index inside the sequence, 1, 0, 0}.  Sequences are ordered by the length of the loop one
+// {tile index inside the sequence, 1, sequence index, 0}.  Sequences are ordered by the length of the loop one
 // of their tiles runs -- the key tile count for query tiles, the query tile count for key tiles --
 // longest first (a counting sort over tile counts; ties keep no particular order, which does not
 // matter because no result depends on which block computes which tile), and inside a sequence
@@ -44,7 +44,7 @@ __device__ void plan_build(const int* __restrict__ cu_q, const int* __restrict__
             const int nt = own_tiles(ql, kl);
             for (int t = 0; t < nt && run < max_tiles; ++t, ++run) {
                 plan[2 * run] = make_int4(qs, ql, ks, kl);
-                plan[2 * run + 1] = make_int4(nt - 1 - t, 1, 0, 0);
+                plan[2 * run + 1] = make_int4(nt - 1 - t, 1, b, 0);
             }
         }
     }
@@ -89,7 +89,7 @@ __device__ void plan_build(const int* __restrict__ cu_q, const int* __restrict__
         for (int t = 0; t < nt; ++t)
             if (first + t < max_tiles) {
                 plan[2 * (first + t)] = make_int4(qs, ql, ks, kl);
-                plan[2 * (first + t) + 1] = make_int4(nt - 1 - t, 1, 0, 0);
+                plan[2 * (first + t) + 1] = make_int4(nt - 1 - t, 1, b, 0);
             }
     }
     __syncthreads();
@@ -104,6 +104,17 @@ varlen_plan_kernel(const int* __restrict__ cu_q, const int* __restrict__ cu_k, i
     __shared__ int part[PLAN_NT];
     plan_build(cu_q, cu_k, B, true, plan_q, max_tiles_q, hist, start, part);
     if (plan_k) plan_build(cu_q, cu_k, B, false, plan_k, max_tiles_k, hist, start, part);   // backward only
+}
+
+__global__ void uniform_cu_kernel(int* __restrict__ cu, int B, int N)
+{
+    const int b = blockIdx.x * blockDim.x + threadIdx.x;
+    if (b <= B) cu[b] = b * N;
+}
+
+int launch_uniform_cu(int* cu, int B, int N, void* stream)
+{
+    return launch_kernel(uniform_cu_kernel, dim3((B + 256) / 256), dim3(256), 0, stream, cu, B, N) == hipSuccess ? 0 : -3;
 }
 
 int launch_varlen_plan(const int* cu_q, const int* cu_k, int B, void* plan_q, int max_tiles_q,

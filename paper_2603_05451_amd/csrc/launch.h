@@ -6,6 +6,18 @@
 
 namespace attn {
 
+// Element strides of one tensor in the variable-length kernels: the address of (token t, head h) of
+// sequence s is  base + t * row + s * batch + h * head  (+ the position inside the head dim), t
+// being the token's index in the packed batch.  Packed tensors have batch = 0; a [B, N, ...]
+// tensor whose batch stride is not N rows passes batch = (batch stride) - N * row.
+struct Stride3 {
+    long long batch, row, head;
+};
+struct VarlenStrides {
+    Stride3 q, k, v, o, d_o, dq, dk, dv;
+    long long lse_batch, lse_head;      // lse index = t + s * lse_batch + h * lse_head
+};
+
 struct FwdArgs {
     const void *q, *k, *v;
     void* o;
@@ -18,6 +30,7 @@ struct FwdArgs {
     // max_tiles its size (an upper bound on the number of 128-row query tiles), T = total query rows
     const void* plan = nullptr;
     int T = 0, max_tiles = 0;
+    VarlenStrides st = {};   // variable-length mode: q, k, v, o and lse strides
     bool f16 = false;   // 16-bit storage type of q, k, v, o: bf16 (default) or IEEE fp16
 };
 
@@ -37,6 +50,9 @@ struct BwdArgs {
     int T = 0, max_tiles = 0;
     const void* plan_k = nullptr; // key-tile table (dK/dV kernels) and its size
     int max_tiles_k = 0;
+    VarlenStrides st = {};        // variable-length mode: strides of every tensor and of lse
+    int rows_per_batch = 0;       // variable-length mode, prepare kernel: tokens per sequence when the
+                                  // tensors have a batch stride (equal lengths), 0 for packed tensors
     bool f16 = false;             // as in FwdArgs
 };
 
@@ -74,6 +90,8 @@ struct LdsOptIn {
 // 0 on success, -2 unsupported head dims, -3 launch failure.
 int launch_fwd(const FwdArgs& a);
 int launch_bwd(const BwdArgs& a);
+// cu[b] = b * N for b = 0 .. B (device): the equal-length batch as a packed one.
+int launch_uniform_cu(int* cu, int B, int N, void* stream);
 // Fills the two plan tables of the variable-length entry points on the device: 0 or -3.
 int launch_varlen_plan(const int* cu_q, const int* cu_k, int B, void* plan_q, int max_tiles_q,
                        void* plan_k, int max_tiles_k, void* stream);

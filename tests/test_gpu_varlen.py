@@ -197,7 +197,7 @@ def test_varlen_many_short_sequences(oracle):
 
 def read_tables(ws, B, Tq, Tk):
     """The two tile tables at the head of a backward workspace, as int arrays [entries, 8]:
-    {first query row, query length, first key row, key length, tile, valid, 0, 0}."""
+    {first query row, query length, first key row, key length, tile, valid, sequence index, 0}."""
     mq, mk = Tq // 128 + B, Tk // 128 + B
     off_k = (mq * 32 + 255) // 256 * 256
     tq = ws[:mq * 32].view(torch.int32).reshape(mq, 8).cpu().numpy()
@@ -205,13 +205,15 @@ def read_tables(ws, B, Tq, Tk):
     return tq, tk
 
 
-def check_table(table, want, loop_tiles):
+def check_table(table, want, loop_tiles, index_of):
     """want: set of (q start, q len, k start, k len, tile); loop_tiles(entry) = length of the loop a
-    tile of that sequence runs.  Every wanted tile once, longest loops first, a sequence's tiles
-    contiguous and from last to first, the rest of the table zero."""
+    tile of that sequence runs; index_of: (q start, q len, k start, k len) -> sequence index.  Every
+    wanted tile once, longest loops first, a sequence's tiles contiguous and from last to first, the
+    rest of the table zero."""
     used = table[table[:, 5] == 1]
     assert len(used) == len(want) and {tuple(int(x) for x in e[:5]) for e in used} == want
-    assert (table[len(used):] == 0).all() and (used[:, 6:] == 0).all()
+    assert (table[len(used):] == 0).all() and (used[:, 7] == 0).all()
+    assert all(int(e[6]) == index_of[tuple(int(x) for x in e[:4])] for e in used)
     loops = np.array([loop_tiles(e) for e in used])
     assert (np.diff(loops) <= 0).all()
     seen, i = set(), 0
@@ -248,8 +250,10 @@ def test_plan_tables_list_every_tile_once_longest_first():
     tq, tk = read_tables(ws, B, Tq, Tk)
     tiles = lambda n: (n + 127) // 128
     seqs = [(int(cuq[b]), ql[b], int(cuk[b]), kl[b]) for b in range(B)]
-    check_table(tq, {(*e, t) for e in seqs if e[3] > 0 for t in range(tiles(e[1]))}, lambda e: tiles(int(e[3])))
-    check_table(tk, {(*e, t) for e in seqs for t in range(tiles(e[3]))}, lambda e: tiles(int(e[1])))
+    index_of = {e: b for b, e in enumerate(seqs) if e[1] > 0 or e[3] > 0}      # sequences that own rows are distinct
+    check_table(tq, {(*e, t) for e in seqs if e[3] > 0 for t in range(tiles(e[1]))}, lambda e: tiles(int(e[3])),
+                index_of)
+    check_table(tk, {(*e, t) for e in seqs for t in range(tiles(e[3]))}, lambda e: tiles(int(e[1])), index_of)
 
 
 def cross_inputs(qlens, klens, H, Hkv, dqk, dv, seed):
