@@ -78,7 +78,10 @@ __device__ __forceinline__ float fast_log2(float x) { return __builtin_amdgcn_lo
 // rows: x = ((row & 3) << 2) | ((row >> 2) & 3).  With 8 or 24 chunks per row (D = 64,
 // 192) rows alternate between bank 0 and bank 32, the XOR stays inside an aligned group
 // of 8 chunks, and the same two conditions give, with y = row >> 1,
-// x = ((y & 1) << 2) | ((y >> 1) & 3).
+// x = ((y & 1) << 2) | ((y >> 1) & 3).  With 12 chunks per row (D = 96) the rows start at chunk
+// offsets 0, 12, 8, 4 (mod 16): four consecutive rows already occupy four different 4-chunk
+// groups, rows four apart coincide, and an XOR inside the aligned group of 4 chunks (the widest
+// that stays inside a 12-chunk row) with x = (row >> 2) & 3 separates those.
 // ---------------------------------------------------------------------------------------
 template <int D>
 __device__ __forceinline__ int swz_chunk(int row, int chunk)
@@ -86,6 +89,9 @@ __device__ __forceinline__ int swz_chunk(int row, int chunk)
     constexpr int CPR = D / 8;
     if constexpr (CPR % 16 == 0) {
         return chunk ^ (((row & 3) << 2) | ((row >> 2) & 3));
+    } else if constexpr (CPR % 8 != 0) {
+        static_assert(CPR % 4 == 0, "head dims are multiples of 32");
+        return chunk ^ ((row >> 2) & 3);
     } else {
         const int y = row >> 1;
         return chunk ^ (((y & 1) << 2) | ((y >> 1) & 3));

@@ -46,7 +46,7 @@ def test_workspace_size(L):
     assert A.attn_bwd_workspace_bytes(1, 2, 2, 128, 64, 64) == 2 * 1024
     assert A.attn_bwd_workspace_bytes(1, 3, 2, 128, 64, 64) == 0      # H % Hkv != 0
     assert A.attn_bwd_workspace_bytes(1, 2, 2, 100, 64, 64) == 0      # N not a multiple of 128
-    assert A.attn_bwd_workspace_bytes(1, 2, 2, 128, 96, 96) == 0      # unsupported head dim
+    assert A.attn_bwd_workspace_bytes(1, 2, 2, 128, 80, 80) == 0      # unsupported head dim
 
 
 def test_forward_argument_validation(L):
@@ -107,7 +107,7 @@ def test_varlen_workspace_and_validation(L):
     bwd_x = A.attn_varlen_workspace_bytes(3, 1000, 5000, 4, 2, 128, 128, True)
     assert bwd_x == 512 + 1536 + 2 * 16128              # 42 key-tile entries -> 1344 -> 1536; statistics sized by Tq
     assert A.attn_varlen_workspace_bytes(3, 1000, 1000, 3, 2, 128, 128, False) == 0      # H % Hkv != 0
-    assert A.attn_varlen_workspace_bytes(3, 1000, 1000, 4, 2, 96, 96, False) == 0        # unsupported head dim
+    assert A.attn_varlen_workspace_bytes(3, 1000, 1000, 4, 2, 80, 80, False) == 0        # unsupported head dim
     assert A.attn_varlen_workspace_bytes(0, 1000, 1000, 4, 2, 64, 64, False) == 0
     assert A.attn_varlen_workspace_bytes(3, 1000, 0, 4, 2, 64, 64, False) == 0           # no keys at all
     p = ctypes.c_void_p(0x1000)
@@ -132,7 +132,7 @@ def test_strided_validation(L):
     assert A.attn_strided_workspace_bytes(2, 4, 2, 100, 64, 64, True) == 256 + \
         A.attn_varlen_workspace_bytes(2, 200, 200, 4, 2, 64, 64, True)
     assert A.attn_strided_workspace_bytes(2, 4, 2, 0, 64, 64, True) == 0
-    assert A.attn_strided_workspace_bytes(2, 4, 2, 100, 96, 96, True) == 0
+    assert A.attn_strided_workspace_bytes(2, 4, 2, 100, 80, 80, True) == 0
     p = ctypes.c_void_p(0x1000)
     ok = ctypes.byref(A.AttnStrides(100 * 4 * 64, 4 * 64, 64))
     call = lambda sq, so, N=100: L.attn_fwd_strided(A.ATTN_BF16, p, sq, p, ok, p, ok, p, so, p, 2, 4, 4, N, 64, 64,

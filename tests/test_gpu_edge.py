@@ -95,7 +95,7 @@ def test_errors_raise_and_leave_outputs_untouched():
     assert e.value.code == A.ATTN_EUNSUPPORTED
     torch.cuda.synchronize()
     assert (o == 7.0).all()
-    q = torch.zeros((1, 128, 2, 96), dtype=torch.bfloat16, device="cuda")      # unsupported head dim
+    q = torch.zeros((1, 128, 2, 80), dtype=torch.bfloat16, device="cuda")      # unsupported head dim
     with pytest.raises(A.AttnError):
         A.attn_fwd(q, q, q, 0.1, False)
 

@@ -14,6 +14,7 @@ pytestmark = pytest.mark.gpu
 
 CASES = [
     I.Workload("h_d64_c", 2, 4, 2, 384, 64, 64, True, 61),
+    I.Workload("h_d96_c", 1, 4, 2, 384, 96, 96, True, 66),
     I.Workload("h_d128_nc", 1, 4, 4, 512, 128, 128, False, 62),
     I.Workload("h_d128_c_gqa", 2, 4, 1, 384, 128, 128, True, 63),
     I.Workload("h_d192_c", 1, 2, 2, 384, 192, 128, True, 64),

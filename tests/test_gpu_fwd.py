@@ -21,6 +21,8 @@ SMALL = [
     I.CANARY,
     I.Workload("s_d64_c", 2, 4, 2, 384, 64, 64, True, 11),
     I.Workload("s_d64_nc", 1, 3, 1, 256, 64, 64, False, 12),
+    I.Workload("s_d96_c", 2, 4, 2, 384, 96, 96, True, 18),
+    I.Workload("s_d96_nc", 1, 3, 3, 640, 96, 96, False, 19),
     I.Workload("s_d128_nc", 2, 4, 4, 384, 128, 128, False, 13),
     I.Workload("s_d128_c", 2, 4, 2, 640, 128, 128, True, 14),
     I.Workload("s_d192_c", 1, 4, 2, 384, 192, 128, True, 15),

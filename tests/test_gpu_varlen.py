@@ -30,6 +30,8 @@ def packed_inputs(lengths, H, Hkv, dqk, dv, seed, with_do=False):
 CASES = [
     ("d64_nc", LENGTHS_A, 4, 2, 64, 64, False, 31),
     ("d64_c", LENGTHS_A, 2, 2, 64, 64, True, 32),
+    ("d96_c", LENGTHS_A, 4, 2, 96, 96, True, 37),
+    ("d96_nc", LENGTHS_B, 2, 2, 96, 96, False, 38),
     ("d128_nc", LENGTHS_A, 4, 1, 128, 128, False, 33),
     ("d128_c", LENGTHS_A, 4, 2, 128, 128, True, 34),
     ("d192_c", LENGTHS_B, 2, 1, 192, 128, True, 35),
@@ -276,6 +278,7 @@ CROSS_C = ([1, 1, 64, 129, 0, 100, 128, 333, 5], [1000, 1, 200, 129, 300, 611, 6
 CROSS_CASES = [
     ("d64_nc", CROSS_NC, 4, 2, 64, 64, False, 61),
     ("d64_c", CROSS_C, 2, 1, 64, 64, True, 62),
+    ("d96_c", CROSS_C, 4, 2, 96, 96, True, 67),
     ("d128_nc", CROSS_NC, 4, 2, 128, 128, False, 63),
     ("d128_c", CROSS_C, 4, 1, 128, 128, True, 64),
     ("d192_nc", CROSS_NC, 2, 2, 192, 128, False, 65),
