@@ -127,6 +127,15 @@ int attn_varlen_fwd(const void* q, const void* k, const void* v, void* o, float*
                     const int* cu_seqlens_q, const int* cu_seqlens_k, int B, int total_q, int total_k,
                     int H, int Hkv, int d_qk, int d_v,
                     float scale, int causal, void* workspace, size_t workspace_bytes, void* stream);
+/* The tile tables alone (paper Sec. 3.3: the sort's metadata can be cached).  Fills both tables
+ * at the head of a workspace of the backward = 1 size.  A later attn_varlen_fwd / attn_varlen_bwd
+ * (or _dtype) call on that workspace with the SAME B, total_q, total_k, H, Hkv and head dims may
+ * then pass cu_seqlens_q = cu_seqlens_k = NULL: it skips the plan kernel and uses the tables as
+ * they are (a backward call needs tables written by this function or by an earlier backward call;
+ * a forward call with non-NULL cu_seqlens writes the query table only).  Calls never modify the
+ * tables otherwise; results are bit-identical to those of calls that rebuild them. */
+int attn_varlen_plan(const int* cu_seqlens_q, const int* cu_seqlens_k, int B, int total_q, int total_k,
+                     int H, int Hkv, int d_qk, int d_v, void* workspace, size_t workspace_bytes, void* stream);
 /* Backward of attn_varlen_fwd (paper Sec. 2.1 second display, per sequence): o and lse must be that
  * call's outputs for the same arguments; dk and dv are summed over the query heads of each group.
  * Every row of dq, dk, dv is written (dk = dv = 0 for the keys of a sequence without queries).

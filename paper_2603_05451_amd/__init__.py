@@ -64,6 +64,8 @@ def lib():
         L.attn_fwd_strided.restype = i
         L.attn_bwd_strided.argtypes = [i] + [vp, sp] * 5 + [vp] + [vp, sp] * 3 + [i] * 6 + [f, i, vp, sz, vp]
         L.attn_bwd_strided.restype = i
+        L.attn_varlen_plan.argtypes = [vp, vp] + [i] * 7 + [vp, sz, vp]
+        L.attn_varlen_plan.restype = i
         L.attn_varlen_fwd.argtypes = [vp] * 7 + [i] * 7 + [f, i, vp, sz, vp]
         L.attn_varlen_fwd.restype = i
         L.attn_varlen_bwd.argtypes = [vp] * 11 + [i] * 7 + [f, i, vp, sz, vp]
@@ -156,24 +158,41 @@ def attn_varlen_workspace_bytes(B, total_q, total_k, H, Hkv, d_qk, d_v, backward
     return int(lib().attn_varlen_workspace_bytes(B, total_q, total_k, H, Hkv, d_qk, d_v, int(bool(backward))))
 
 
+def attn_varlen_plan(cu_seqlens, total_q, total_k, H, Hkv, d_qk, d_v, workspace, cu_seqlens_k=None, stream=None):
+    """Fills the tile tables of a backward-sized workspace once; later attn_varlen_fwd / attn_varlen_bwd
+    calls on it may pass cu_seqlens=None and B=<number of sequences> to reuse them."""
+    B = cu_seqlens.numel() - 1
+    if cu_seqlens_k is None:
+        cu_seqlens_k = cu_seqlens
+    _check(lib().attn_varlen_plan(_dev_cu(cu_seqlens, B), _dev_cu(cu_seqlens_k, B, "cu_seqlens_k"), B, total_q, total_k,
+                                  H, Hkv, d_qk, d_v, ctypes.c_void_p(workspace.data_ptr()), workspace.numel(),
+                                  _stream(stream)))
+
+
 def _dev_cu(cu, B, name="cu_seqlens"):
     import torch
+    if cu is None:
+        return None
     if not (cu.is_cuda and cu.dtype == torch.int32 and cu.is_contiguous() and tuple(cu.shape) == (B + 1,)):
         raise ValueError(f"{name} must be a contiguous int32 CUDA tensor [B+1]")
     return ctypes.c_void_p(cu.data_ptr())
 
 
 def attn_varlen_fwd(q, k, v, cu_seqlens, scale, causal, o=None, lse=None, workspace=None, stream=None,
-                    cu_seqlens_k=None):
+                    cu_seqlens_k=None, B=None):
     """Packed variable-length batch: q [Tq,H,d_qk], k [Tk,Hkv,d_qk], v [Tk,Hkv,d_v] bf16 (or all fp16),
     cu_seqlens [B+1] int32 (query rows; also the key rows unless cu_seqlens_k is given), all on the
     GPU -> (o [Tq,H,d_v], lse [H,Tq] fp32)."""
     import torch
     T, H, dqk = q.shape
     Tk, Hkv, dv = k.shape[0], k.shape[1], v.shape[2]
-    B = cu_seqlens.numel() - 1
-    if cu_seqlens_k is None:
-        cu_seqlens_k = cu_seqlens
+    if cu_seqlens is None:       # tables kept in `workspace` by attn_varlen_plan or an earlier call
+        if B is None or workspace is None:
+            raise ValueError("cu_seqlens=None needs B and the workspace that holds the tables")
+    else:
+        B = cu_seqlens.numel() - 1
+        if cu_seqlens_k is None:
+            cu_seqlens_k = cu_seqlens
     if o is None:
         o = torch.empty((T, H, dv), dtype=q.dtype, device=q.device)
     if lse is None:
@@ -194,14 +213,18 @@ def attn_varlen_fwd(q, k, v, cu_seqlens, scale, causal, o=None, lse=None, worksp
 
 
 def attn_varlen_bwd(q, k, v, o, d_o, lse, cu_seqlens, scale, causal, dq=None, dk=None, dv=None, workspace=None,
-                    stream=None, cu_seqlens_k=None):
+                    stream=None, cu_seqlens_k=None, B=None):
     """Backward of attn_varlen_fwd: returns (dq [Tq,H,d_qk], dk [Tk,Hkv,d_qk], dv [Tk,Hkv,d_v])."""
     import torch
     T, H, dqk = q.shape
     Tk, Hkv, dv_ = k.shape[0], k.shape[1], v.shape[2]
-    B = cu_seqlens.numel() - 1
-    if cu_seqlens_k is None:
-        cu_seqlens_k = cu_seqlens
+    if cu_seqlens is None:       # tables kept in `workspace` by attn_varlen_plan or an earlier backward call
+        if B is None or workspace is None:
+            raise ValueError("cu_seqlens=None needs B and the workspace that holds the tables")
+    else:
+        B = cu_seqlens.numel() - 1
+        if cu_seqlens_k is None:
+            cu_seqlens_k = cu_seqlens
     dq = torch.empty_like(q) if dq is None else dq
     dk = torch.empty_like(k) if dk is None else dk
     dv = torch.empty_like(v) if dv is None else dv

@@ -200,7 +200,7 @@ int varlen_fwd_run(int dtype, const void* q, const void* k, const void* v, void*
                    float scale, int causal, char* ws, const attn::VarlenStrides& st, void* stream)
 {
     const VarlenLayout w = varlen_layout(B, Tq, Tk, H);
-    if (attn::launch_varlen_plan(cu_q, cu_k, B, ws + w.plan_q_off, w.max_tiles_q, nullptr, 0, stream) != 0)
+    if (cu_q && attn::launch_varlen_plan(cu_q, cu_k, B, ws + w.plan_q_off, w.max_tiles_q, nullptr, 0, stream) != 0)
         return ATTN_ELAUNCH;
     attn::FwdArgs a{q, k, v, o, lse, B, H, Hkv, 0, d_qk, d_v, scale, causal != 0, stream};
     a.plan = ws + w.plan_q_off;
@@ -218,8 +218,8 @@ int varlen_bwd_run(int dtype, const void* q, const void* k, const void* v, const
                    float scale, int causal, char* ws, const attn::VarlenStrides& st, int rows_per_batch, void* stream)
 {
     const VarlenLayout w = varlen_layout(B, Tq, Tk, H);
-    if (attn::launch_varlen_plan(cu_q, cu_k, B, ws + w.plan_q_off, w.max_tiles_q,
-                                 ws + w.plan_k_off, w.max_tiles_k, stream) != 0)
+    if (cu_q && attn::launch_varlen_plan(cu_q, cu_k, B, ws + w.plan_q_off, w.max_tiles_q,
+                                         ws + w.plan_k_off, w.max_tiles_k, stream) != 0)
         return ATTN_ELAUNCH;
     attn::BwdArgs a{q, k, v, o, d_o, lse, dq, dk, dv, B, H, Hkv, 0, d_qk, d_v, scale, causal != 0,
                     reinterpret_cast<float*>(ws + w.d_off), reinterpret_cast<float*>(ws + w.lse2_off),
@@ -245,13 +245,27 @@ size_t attn_varlen_workspace_bytes(int B, int total_q, int total_k, int H, int H
     return backward ? w.total_bwd : w.total_fwd;
 }
 
+int attn_varlen_plan(const int* cu_seqlens_q, const int* cu_seqlens_k, int B, int total_q, int total_k,
+                     int H, int Hkv, int d_qk, int d_v, void* workspace, size_t workspace_bytes, void* stream)
+{
+    if (!cu_seqlens_q || !cu_seqlens_k || !workspace) return ATTN_EINVAL;
+    if (int rc = check_varlen(B, total_q, total_k, H, Hkv, d_qk, d_v)) return rc;
+    if (misaligned(cu_seqlens_q, 4) || misaligned(cu_seqlens_k, 4) || misaligned(workspace, 256)) return ATTN_EINVAL;
+    const VarlenLayout w = varlen_layout(B, total_q, total_k, H);
+    if (workspace_bytes < w.total_bwd) return ATTN_EINVAL;
+    char* ws = static_cast<char*>(workspace);
+    return attn::launch_varlen_plan(cu_seqlens_q, cu_seqlens_k, B, ws + w.plan_q_off, w.max_tiles_q,
+                                    ws + w.plan_k_off, w.max_tiles_k, stream) == 0 ? ATTN_OK : ATTN_ELAUNCH;
+}
+
 int attn_varlen_fwd_dtype(int dtype, const void* q, const void* k, const void* v, void* o, float* lse,
                           const int* cu_seqlens_q, const int* cu_seqlens_k, int B, int total_q, int total_k,
                           int H, int Hkv, int d_qk, int d_v,
                           float scale, int causal, void* workspace, size_t workspace_bytes, void* stream)
 {
     if (dtype != ATTN_BF16 && dtype != ATTN_F16) return ATTN_EUNSUPPORTED;
-    if (!q || !k || !v || !o || !lse || !cu_seqlens_q || !cu_seqlens_k || !workspace) return ATTN_EINVAL;
+    if (!q || !k || !v || !o || !lse || !workspace) return ATTN_EINVAL;
+    if ((cu_seqlens_q == nullptr) != (cu_seqlens_k == nullptr)) return ATTN_EINVAL;   // both null: tables kept
     if (int rc = check_varlen(B, total_q, total_k, H, Hkv, d_qk, d_v)) return rc;
     if (!(scale > 0.0f) || !(scale < 1e30f)) return ATTN_EINVAL;
     if (misaligned(q, 16) || misaligned(k, 16) || misaligned(v, 16) || misaligned(o, 16) ||
@@ -279,8 +293,8 @@ int attn_varlen_bwd_dtype(int dtype, const void* q, const void* k, const void* v
                           float scale, int causal, void* workspace, size_t workspace_bytes, void* stream)
 {
     if (dtype != ATTN_BF16 && dtype != ATTN_F16) return ATTN_EUNSUPPORTED;
-    if (!q || !k || !v || !o || !d_o || !lse || !dq || !dk || !dv || !cu_seqlens_q || !cu_seqlens_k || !workspace)
-        return ATTN_EINVAL;
+    if (!q || !k || !v || !o || !d_o || !lse || !dq || !dk || !dv || !workspace) return ATTN_EINVAL;
+    if ((cu_seqlens_q == nullptr) != (cu_seqlens_k == nullptr)) return ATTN_EINVAL;   // both null: tables kept
     if (int rc = check_varlen(B, total_q, total_k, H, Hkv, d_qk, d_v)) return rc;
     if (!(scale > 0.0f) || !(scale < 1e30f)) return ATTN_EINVAL;
     const void* ptrs[] = {q, k, v, o, d_o, dq, dk, dv};

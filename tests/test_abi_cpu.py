@@ -115,13 +115,17 @@ def test_varlen_workspace_and_validation(L):
     call = lambda *a: L.attn_varlen_fwd(*a)
     ok_tail = (3, 1000, 1000, 4, 2, 128, 128, 0.1, 0, w, 1 << 20, None)
     assert call(None, p, p, p, p, p, p, *ok_tail) == A.ATTN_EINVAL
-    assert call(p, p, p, p, p, None, p, *ok_tail) == A.ATTN_EINVAL                 # cu_seqlens_q missing
-    assert call(p, p, p, p, p, p, None, *ok_tail) == A.ATTN_EINVAL                 # cu_seqlens_k missing
+    assert call(p, p, p, p, p, None, p, *ok_tail) == A.ATTN_EINVAL                 # one of the two arrays missing
+    assert call(p, p, p, p, p, p, None, *ok_tail) == A.ATTN_EINVAL                 # (both missing = cached tables)
     assert call(p, p, p, p, p, p, p, 3, 1000, 1000, 4, 2, 128, 128, 0.1, 0, w, 16, None) == A.ATTN_EINVAL   # workspace too small
     assert call(p, p, p, p, p, p, p, 3, 1000, 1000, 4, 2, 80, 80, 0.1, 0, w, 1 << 20, None) == A.ATTN_EUNSUPPORTED
     assert call(p, p, p, p, p, p, p, 3, 1000, 1000, 4, 2, 128, 128, -1.0, 0, w, 1 << 20, None) == A.ATTN_EINVAL
     assert L.attn_varlen_bwd(p, p, p, p, p, p, p, p, p, p, p, 3, 1000, 1000, 4, 2, 128, 128, 0.1, 0, w, 256,
                              None) == A.ATTN_EINVAL
+    # plan tables alone: needs both arrays and a backward-sized workspace
+    assert L.attn_varlen_plan(p, None, 3, 1000, 1000, 4, 2, 128, 128, w, 1 << 20, None) == A.ATTN_EINVAL
+    assert L.attn_varlen_plan(p, p, 3, 1000, 1000, 4, 2, 128, 128, w, fwd, None) == A.ATTN_EINVAL
+    assert L.attn_varlen_plan(p, p, 3, 1000, 1000, 4, 2, 80, 80, w, 1 << 20, None) == A.ATTN_EUNSUPPORTED
 
 
 def test_strided_validation(L):

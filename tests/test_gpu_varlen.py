@@ -346,3 +346,25 @@ def test_varlen_decode_step_matches_last_row_of_prefill():
     torch.cuda.synchronize()
     assert (o_dec.float() - o_full[last].float()).abs().max().item() <= 2e-2
     assert (lse_dec - lse_full[:, last]).abs().max().item() <= 2 * LSE_ABS
+
+
+def test_cached_plan_tables_give_identical_results():
+    """attn_varlen_plan once, then forward and backward calls without cu_seqlens (paper Sec. 3.3:
+    the sort's metadata can be cached): bit-identical to calls that rebuild the tables."""
+    import paper_2603_05451_amd as A
+    qlens, klens = CROSS_C
+    H, Hkv, d = 4, 2, 128
+    x, cuq, cuk, scale = cross_inputs(qlens, klens, H, Hkv, d, d, 72)
+    q, k, v, do = (x[n].cuda() for n in ("q", "k", "v", "do"))
+    cuqd, cukd = torch.from_numpy(cuq).cuda(), torch.from_numpy(cuk).cuda()
+    o, lse = A.attn_varlen_fwd(q, k, v, cuqd, scale, True, cu_seqlens_k=cukd)
+    ref = A.attn_varlen_bwd(q, k, v, o, do, lse, cuqd, scale, True, cu_seqlens_k=cukd)
+    B, Tq, Tk = len(qlens), q.shape[0], k.shape[0]
+    ws = torch.zeros(A.attn_varlen_workspace_bytes(B, Tq, Tk, H, Hkv, d, d, True), dtype=torch.uint8, device="cuda")
+    A.attn_varlen_plan(cuqd, Tq, Tk, H, Hkv, d, d, ws, cu_seqlens_k=cukd)
+    for _ in range(2):                                   # the tables survive the calls that use them
+        o2, lse2 = A.attn_varlen_fwd(q, k, v, None, scale, True, workspace=ws, B=B)
+        got = A.attn_varlen_bwd(q, k, v, o2, do, lse2, None, scale, True, workspace=ws, B=B)
+        torch.cuda.synchronize()
+        assert torch.equal(o2, o) and torch.equal(lse2, lse)
+        assert all(torch.equal(a, b) for a, b in zip(got, ref))
