@@ -1,0 +1,130 @@
+"""Two more GPU checks of the C-ABI entry points: capture in a HIP graph (the library allocates
+nothing and enqueues only kernels, so a captured call must replay correctly on new data), and a
+seeded sweep over random small shapes and length mixes against the fp64 oracle."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2603_05451_amd import inputs as I
+from parity import LSE_ABS, term_magnitudes
+
+pytestmark = pytest.mark.gpu
+
+
+def test_fixed_and_varlen_calls_replay_in_a_hip_graph():
+    """Forward + backward (fixed-length and packed) captured once, replayed three times on
+    different inputs with eager work in between; every replay equals the eager result bit for bit."""
+    import paper_2603_05451_amd as A
+    w = I.Workload("graph", 2, 4, 2, 384, 128, 128, True, 91)
+    lens = [300, 129, 64, 275]
+    T = sum(lens)
+    cu = torch.tensor(np.concatenate([[0], np.cumsum(lens)]), dtype=torch.int32, device="cuda")
+
+    def fresh(seed):
+        x = I.make_inputs(I.Workload("g", w.B, w.H, w.Hkv, w.N, w.dqk, w.dv, True, seed))
+        return [x[n].cuda() for n in ("q", "k", "v", "do")]
+
+    q, k, v, do = fresh(91)
+    o = torch.empty_like(q)
+    lse = torch.empty((w.B, w.H, w.N), dtype=torch.float32, device="cuda")
+    dq, dk, dv = torch.empty_like(q), torch.empty_like(k), torch.empty_like(v)
+    ws = torch.empty(A.attn_bwd_workspace_bytes(w.B, w.H, w.Hkv, w.N, w.dqk, w.dv), dtype=torch.uint8, device="cuda")
+    # the packed call works on the first T rows of the same buffers, seen as [T, heads, d]
+    pk = lambda t: t.reshape(-1, *t.shape[2:])[:T]
+    ov = torch.empty((T, w.H, w.dv), dtype=torch.bfloat16, device="cuda")
+    lsev = torch.empty((w.H, T), dtype=torch.float32, device="cuda")
+    dqv, dkv, dvv = torch.empty_like(pk(q)), torch.empty_like(pk(k)), torch.empty_like(pk(v))
+    wsv = torch.empty(A.attn_varlen_workspace_bytes(len(lens), T, T, w.H, w.Hkv, w.dqk, w.dv, True),
+                      dtype=torch.uint8, device="cuda")
+
+    def step():
+        A.attn_fwd(q, k, v, w.scale, True, o=o, lse=lse)
+        A.attn_bwd(q, k, v, o, do, lse, w.scale, True, dq=dq, dk=dk, dv=dv, workspace=ws)
+        A.attn_varlen_fwd(pk(q), pk(k), pk(v), cu, w.scale, True, o=ov, lse=lsev, workspace=wsv)
+        A.attn_varlen_bwd(pk(q), pk(k), pk(v), ov, pk(do), lsev, cu, w.scale, True, dq=dqv, dk=dkv, dv=dvv,
+                          workspace=wsv)
+
+    outs = (o, lse, dq, dk, dv, ov, lsev, dqv, dkv, dvv)
+    step()                                              # warm-up outside the capture (first-call set-up)
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(g, stream=side):
+            step()
+    torch.cuda.current_stream().wait_stream(side)
+    for seed in (92, 93, 94):
+        for dst, src in zip((q, k, v, do), fresh(seed)):
+            dst.copy_(src)
+        for t in outs:
+            t.zero_()
+        g.replay()
+        torch.cuda.synchronize()
+        got = [t.clone() for t in outs]
+        assert got[0].float().abs().sum().item() > 0
+        for t in outs:
+            t.zero_()
+        step()                                          # eager, same inputs
+        torch.cuda.synchronize()
+        assert all(torch.equal(a, b) for a, b in zip(got, outs)), f"replay with seed {seed} differs from eager"
+
+
+def test_random_shapes_and_length_mixes(oracle):
+    """24 seeded random cases: head dim, group size, causal flag, number of sequences and per-sequence
+    query / key counts (including 0 and 1) drawn at random; forward and backward through the
+    variable-length entry points against the oracle, element by element."""
+    import paper_2603_05451_amd as A
+    rng = np.random.default_rng(2024)
+    # Gate: the absolute bound of the N(0,1) tolerance plus the first-order rounding terms of
+    # parity.py (output rounding and the bf16 rounding of P, dS and O, scaled by the sizes of the
+    # summed terms): with a handful of keys or queries the gradients are sums of a few hundred
+    # large cancelling terms, which the plain 2e-2 does not cover.
+    excess = lambda got, ref, mag: float((np.abs(got - ref) - (2e-2 + 2.0 ** -8 * (np.abs(ref) + mag))).max())
+    for case in range(24):
+        dqk, dv = [(64, 64), (96, 96), (128, 128), (192, 128)][case % 4]
+        Hkv = int(rng.integers(1, 3))
+        H = Hkv * int(rng.integers(1, 4))
+        causal = bool(rng.integers(0, 2))
+        B = int(rng.integers(1, 7))
+        klens = [int(n) for n in rng.choice([1, 2, 31, 64, 65, 127, 128, 129, 200, 257, 300], B)]
+        if case % 3 == 0:                                # self-attention
+            qlens = list(klens)
+        elif causal:                                     # no more queries than keys under a causal mask
+            qlens = [int(rng.integers(0, n + 1)) for n in klens]
+        else:
+            qlens = [int(n) for n in rng.choice([0, 1, 5, 64, 100, 129, 260], B)]
+        if sum(qlens) == 0:
+            qlens[0] = 1
+        Tq, Tk = sum(qlens), sum(klens)
+        x = I.make_inputs(I.Workload("rnd", 1, H, Hkv, max(Tq, Tk), dqk, dv, False, 1000 + case))
+        t = {n: x[n][0, :(Tq if n in ("q", "do") else Tk)].contiguous() for n in ("q", "k", "v", "do")}
+        scale = 1.0 / np.sqrt(dqk)
+        cuq = np.concatenate([[0], np.cumsum(qlens)]).astype(np.int32)
+        cuk = np.concatenate([[0], np.cumsum(klens)]).astype(np.int32)
+        q, k, v, do = (t[n].cuda() for n in ("q", "k", "v", "do"))
+        cuqd, cukd = torch.from_numpy(cuq).cuda(), torch.from_numpy(cuk).cuda()
+        o, lse = A.attn_varlen_fwd(q, k, v, cuqd, scale, causal, cu_seqlens_k=cukd)
+        dq, dk, dvv = A.attn_varlen_bwd(q, k, v, o, do, lse, cuqd, scale, causal, cu_seqlens_k=cukd)
+        torch.cuda.synchronize()
+        o, lse, dq, dk, dvv = (z.float().cpu().numpy() for z in (o, lse, dq, dk, dvv))
+        tag = f"case {case}: d{dqk}/{dv} H{H}/{Hkv} causal={causal} q={qlens} k={klens}"
+        for b, (nq, nk) in enumerate(zip(qlens, klens)):
+            sq, sk = slice(int(cuq[b]), int(cuq[b + 1])), slice(int(cuk[b]), int(cuk[b + 1]))
+            if nq == 0:
+                assert (dk[sk] == 0).all() and (dvv[sk] == 0).all(), tag
+                continue
+            pos = np.arange(nq) + (nk - nq)
+            fq, fk, fv, fdo = (I.to_f64(t[m][s][None]) for m, s in (("q", sq), ("k", sk), ("v", sk), ("do", sq)))
+            ro, rlse = oracle.attn_fwd(fq, fk, fv, scale, causal, q_pos=pos)
+            rdq, rdk, rdv = oracle.attn_bwd(fq, fk, fv, fdo, scale, causal, q_pos=pos)
+            assert np.abs(lse[:, sq][None] - rlse).max() <= LSE_ABS, tag
+            G = H // Hkv
+            worst = -1.0
+            for g in range(Hkv):
+                hs = slice(g * G, (g + 1) * G)
+                a_o, a_dq, a_dk, a_dv = term_magnitudes(fq[0][:, hs], fk[0][:, g], fv[0][:, g], fdo[0][:, hs], scale,
+                                                        causal, q_pos=pos)
+                worst = max(worst, excess(o[sq][:, hs], ro[0][:, hs], a_o), excess(dq[sq][:, hs], rdq[0][:, hs], a_dq),
+                            excess(dk[sk][:, g], rdk[0][:, g], a_dk), excess(dvv[sk][:, g], rdv[0][:, g], a_dv))
+            assert worst <= 0, f"{tag}, sequence {b}: excess {worst:.3e}"
