@@ -178,7 +178,7 @@ def main():
         write_varlen_table(args.varlen_table, [I.VARLEN_MIX, I.VARLEN_MIX_GQA, I.VARLEN_MIX_D64])
         return
 
-    named = {w.name: w for w in [I.CANARY, I.TARGET, I.GQA, I.D96, I.MLA_OUTLIER] + I.SWEEP_D64_NC + I.SWEEP_D128_C}
+    named = {w.name: w for w in [I.CANARY, I.TARGET, I.GQA, I.D96, I.D256, I.MLA_OUTLIER] + I.SWEEP_D64_NC + I.SWEEP_D128_C}
     named["target"] = I.TARGET
     w = named[args.workload]
     x = I.make_inputs(w)
@@ -260,7 +260,7 @@ def main():
         out["cpu_baseline"] = cpu_baseline(w, x)
     if args.table:
         del q, k, v, do, o, lse, dq, dk, dv, ws
-        write_table(args.table, [I.CANARY] + I.SWEEP_D64_NC + I.SWEEP_D128_C + [I.TARGET, I.GQA, I.D96, I.MLA_OUTLIER])
+        write_table(args.table, [I.CANARY] + I.SWEEP_D64_NC + I.SWEEP_D128_C + [I.TARGET, I.GQA, I.D96, I.D256, I.MLA_OUTLIER])
     print(json.dumps(out))
 
 

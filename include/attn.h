@@ -25,7 +25,7 @@
  *   - Grouped-query attention: H % Hkv == 0; query head h reads KV head h / (H / Hkv);
  *     dk and dv are summed over the query heads of each group.
  *   - causal != 0: key j is visible to query i iff j <= i.
- *   - Supported shapes: (d_qk, d_v) in {(64,64), (96,96), (128,128), (192,128)}; N a positive
+ *   - Supported shapes: (d_qk, d_v) in {(64,64), (96,96), (128,128), (192,128), (256,256)}; N a positive
  *     multiple of 128 (the attn_varlen_* entry points take any lengths).
  *   - Return value: ATTN_OK, or a negative code.  On any error nothing has been
  *     enqueued and no output has been touched.

@@ -10,7 +10,7 @@ namespace {
 bool dims_supported(int d_qk, int d_v)
 {
     return (d_qk == 64 && d_v == 64) || (d_qk == 96 && d_v == 96) || (d_qk == 128 && d_v == 128) ||
-           (d_qk == 192 && d_v == 128);
+           (d_qk == 192 && d_v == 128) || (d_qk == 256 && d_v == 256);
 }
 
 bool misaligned(const void* p, uintptr_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) != 0; }
@@ -433,8 +433,8 @@ const char* attn_strerror(int code)
         case ATTN_OK: return "success";
         case ATTN_EINVAL: return "invalid argument (null or misaligned pointer, bad size, H % Hkv != 0, "
                                  "non-positive scale, or workspace too small)";
-        case ATTN_EUNSUPPORTED: return "unsupported shape: (d_qk, d_v) must be (64,64), (96,96), (128,128) or "
-                                       "(192,128) and N a multiple of 128";
+        case ATTN_EUNSUPPORTED: return "unsupported shape: (d_qk, d_v) must be (64,64), (96,96), (128,128), "
+                                       "(192,128) or (256,256) and N a multiple of 128";
         case ATTN_ELAUNCH: return "HIP kernel launch failed";
         default: return "unknown error code";
     }

@@ -54,6 +54,7 @@ CANARY = Workload("canary_N128_d64", 1, 2, 2, 128, 64, 64, False, 0)
 TARGET = Workload("target_N8192_d128_nc", 2, 16, 16, 8192, 128, 128, False, 6)
 GQA = Workload("gqa_N8192_d128_c", 2, 32, 8, 8192, 128, 128, True, 4)
 D96 = Workload("d96_N8192_c", 2, 16, 16, 8192, 96, 96, True, 10)      # a head dim between the paper's 64 and 128
+D256 = Workload("d256_N8192_c", 2, 8, 8, 8192, 256, 256, True, 12)     # hidden = 2048 like the paper's settings
 MLA_OUTLIER = Workload("d192x128_N32768_c_outliers", 1, 16, 16, 32768, 192, 128, True, 5,
                        outlier_frac=0.01)
 SWEEP_D64_NC = sweep(64, False, 2)

@@ -62,7 +62,7 @@ def test_forward_argument_validation(L):
     assert fwd(ctypes.c_void_p(0x1008), p, p, p, p, 1, 2, 2, 128, 64, 64, 0.125, 0, None) == A.ATTN_EINVAL
     assert fwd(p, p, p, p, p, 1, 2, 2, 192, 64, 64, 0.125, 0, None) == A.ATTN_EUNSUPPORTED
     assert fwd(p, p, p, p, p, 1, 2, 2, 128, 128, 64, 0.125, 0, None) == A.ATTN_EUNSUPPORTED
-    assert L.attn_fwd(p, p, p, p, p, 1, 2, 2, 128, 256, 0.125, 0, None) == A.ATTN_EUNSUPPORTED
+    assert L.attn_fwd(p, p, p, p, p, 1, 2, 2, 128, 512, 0.125, 0, None) == A.ATTN_EUNSUPPORTED
 
 
 def test_backward_argument_validation(L):

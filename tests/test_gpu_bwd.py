@@ -29,6 +29,8 @@ SMALL = [
     I.Workload("s_d96_nc", 1, 3, 3, 640, 96, 96, False, 29),
     I.Workload("s_d128_nc", 2, 4, 4, 384, 128, 128, False, 23),
     I.Workload("s_d128_c", 2, 4, 2, 640, 128, 128, True, 24),
+    I.Workload("s_d256_c", 1, 4, 2, 384, 256, 256, True, 20),
+    I.Workload("s_d256_nc", 2, 2, 2, 256, 256, 256, False, 19),
     I.Workload("s_d192_c", 1, 4, 2, 384, 192, 128, True, 25),
     I.Workload("s_d192_nc", 1, 2, 2, 256, 192, 128, False, 26),
     I.Workload("s_d192_c_outl", 1, 2, 1, 512, 192, 128, True, 27, outlier_frac=0.01),

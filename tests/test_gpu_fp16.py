@@ -18,6 +18,7 @@ CASES = [
     I.Workload("h_d128_nc", 1, 4, 4, 512, 128, 128, False, 62),
     I.Workload("h_d128_c_gqa", 2, 4, 1, 384, 128, 128, True, 63),
     I.Workload("h_d192_c", 1, 2, 2, 384, 192, 128, True, 64),
+    I.Workload("h_d256_c", 1, 2, 1, 256, 256, 256, True, 67),
 ]
 
 

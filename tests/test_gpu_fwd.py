@@ -25,6 +25,8 @@ SMALL = [
     I.Workload("s_d96_nc", 1, 3, 3, 640, 96, 96, False, 19),
     I.Workload("s_d128_nc", 2, 4, 4, 384, 128, 128, False, 13),
     I.Workload("s_d128_c", 2, 4, 2, 640, 128, 128, True, 14),
+    I.Workload("s_d256_c", 1, 4, 2, 384, 256, 256, True, 10),
+    I.Workload("s_d256_nc", 2, 2, 2, 256, 256, 256, False, 9),
     I.Workload("s_d192_c", 1, 4, 2, 384, 192, 128, True, 15),
     I.Workload("s_d192_nc", 1, 2, 2, 256, 192, 128, False, 16),
     I.Workload("s_d192_c_outl", 1, 2, 1, 512, 192, 128, True, 17, outlier_frac=0.01),

@@ -71,7 +71,7 @@ def test_fixed_and_varlen_calls_replay_in_a_hip_graph():
 
 
 def test_random_shapes_and_length_mixes(oracle):
-    """24 seeded random cases: head dim, group size, causal flag, number of sequences and per-sequence
+    """25 seeded random cases: head dim, group size, causal flag, number of sequences and per-sequence
     query / key counts (including 0 and 1) drawn at random; forward and backward through the
     variable-length entry points against the oracle, element by element."""
     import paper_2603_05451_amd as A
@@ -81,8 +81,8 @@ def test_random_shapes_and_length_mixes(oracle):
     # summed terms): with a handful of keys or queries the gradients are sums of a few hundred
     # large cancelling terms, which the plain 2e-2 does not cover.
     excess = lambda got, ref, mag: float((np.abs(got - ref) - (2e-2 + 2.0 ** -8 * (np.abs(ref) + mag))).max())
-    for case in range(24):
-        dqk, dv = [(64, 64), (96, 96), (128, 128), (192, 128)][case % 4]
+    for case in range(25):
+        dqk, dv = [(64, 64), (96, 96), (128, 128), (192, 128), (256, 256)][case % 5]
         Hkv = int(rng.integers(1, 3))
         H = Hkv * int(rng.integers(1, 4))
         causal = bool(rng.integers(0, 2))

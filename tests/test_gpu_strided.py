@@ -38,7 +38,7 @@ def test_bhsd_views_match_contiguous_calls_bitwise(dqk, dv, H, Hkv, causal, seed
 
 
 @pytest.mark.parametrize("d,N,causal,seed", [(64, 200, True, 84), (128, 333, False, 85), (128, 1, True, 86),
-                                             (96, 130, True, 88)])
+                                             (96, 130, True, 88), (256, 190, True, 89)])
 def test_fused_qkv_buffer_any_length(oracle, d, N, causal, seed):
     """q, k, v are slices of one [B, N, H + 2 Hkv, d] buffer (the output of a fused projection), the
     gradients slices of another; N is not a multiple of any tile.  Checked against the oracle."""

@@ -35,6 +35,8 @@ CASES = [
     ("d128_nc", LENGTHS_A, 4, 1, 128, 128, False, 33),
     ("d128_c", LENGTHS_A, 4, 2, 128, 128, True, 34),
     ("d192_c", LENGTHS_B, 2, 1, 192, 128, True, 35),
+    ("d256_c", LENGTHS_A, 2, 1, 256, 256, True, 39),
+    ("d256_nc", LENGTHS_B, 2, 2, 256, 256, False, 40),
     ("d192_nc", LENGTHS_B, 2, 2, 192, 128, False, 36),
 ]
 
@@ -102,8 +104,11 @@ def test_varlen_bwd_parity(oracle, name, lengths, H, Hkv, dqk, dv, causal, seed)
             assert_close(dvv[s][None], rdv, f"varlen dV {name} seq{b} len{n}")
             continue
         assert_close(dq[s][None], rdq, f"varlen dQ {name} seq{b} len{n}")
-        assert_close(dk[s][None], rdk, f"varlen dK {name} seq{b} len{n}")
-        assert_close(dvv[s][None], rdv, f"varlen dV {name} seq{b} len{n}")
+        # dK / dV summed over the query heads of a group exceed magnitude 4 on the first keys of a
+        # causal sequence, where half a bf16 ulp of the output is 1.6e-2 already
+        close_kv = assert_close_wide if H != Hkv else assert_close
+        close_kv(dk[s][None], rdk, f"varlen dK {name} seq{b} len{n}")
+        close_kv(dvv[s][None], rdv, f"varlen dV {name} seq{b} len{n}")
 
 
 def test_varlen_bwd_matches_fixed_length_and_is_reproducible():
@@ -282,6 +287,7 @@ CROSS_CASES = [
     ("d128_nc", CROSS_NC, 4, 2, 128, 128, False, 63),
     ("d128_c", CROSS_C, 4, 1, 128, 128, True, 64),
     ("d192_nc", CROSS_NC, 2, 2, 192, 128, False, 65),
+    ("d256_c", CROSS_C, 2, 1, 256, 256, True, 68),
     ("d192_c", CROSS_C, 2, 1, 192, 128, True, 66),
 ]
 
