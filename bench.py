@@ -22,8 +22,8 @@ PEAK_BF16_TFLOPS = 2500.0      # MI355X published dense bf16 MFMA peak
 # --pmc runs, scaled by the same counters' reading for a 1 GiB copy; profiles/bench_target_*.md).
 # They cannot be measured from inside this process; None for any other workload.
 MEASURED_TRAFFIC = {
-    "target_N8192_d128_nc": {"attn_fwd_kernel": 287e6 + 68e6, "attn_bwd_dkdv_ws_kernel": 407e6 + 134e6,
-                             "attn_bwd_dq_kernel": 375e6 + 67e6},
+    "target_N8192_d128_nc": {"attn_fwd_wide_kernel": 201e6 + 68e6, "attn_bwd_dkdv_ws_kernel": 407e6 + 134e6,
+                             "attn_bwd_dq_wide_kernel": 271e6 + 67e6},
 }
 PAPER_CONTEXT = "paper: up to 1613 TFLOP/s forward (71% of 2.25 PFLOP/s) on B200, BF16 -- other hardware, context only"
 
@@ -225,6 +225,10 @@ def main():
     f_dq = 2.0 * pairs * (2 * w.dqk + w.dv)           # S, dQ over d_qk; dP over d_v
     tf = lambda flops, ms: flops / ms / 1e9
     dkdv_name = "attn_bwd_dkdv_ws_kernel" if w.dqk == 128 else "attn_bwd_dkdv_kernel"
+    # at d = 128 and N % 256 == 0 the library runs its 256-query blocks (forward always, dQ without a mask)
+    wide = w.dqk == 128 and w.N % 256 == 0
+    fwd_name = "attn_fwd_wide_kernel" if wide else "attn_fwd_kernel"
+    dq_name = "attn_bwd_dq_wide_kernel" if wide and not w.causal else "attn_bwd_dq_kernel"
     out = {
         "metric": "attention fwd / bwd TFLOPs/s (bf16) and % of MI355X dense BF16 MFMA peak",
         "value": round(tf(f_fwd + f_bwd, ms_step), 2), "unit": "TFLOP/s",
@@ -246,14 +250,14 @@ def main():
                      "achieved": round(tf(f_dkdv, ms_dkdv), 1), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                      "frac": round(tf(f_dkdv, ms_dkdv) / PEAK_BF16_TFLOPS, 4),
                      "traffic": MEASURED_TRAFFIC.get(w.name, {}).get(dkdv_name)},
-        "roofline_dq": {"kernel": "attn_bwd_dq_kernel", "bound": "mfma",
+        "roofline_dq": {"kernel": dq_name, "bound": "mfma",
                         "achieved": round(tf(f_dq, ms_dq), 1), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                         "frac": round(tf(f_dq, ms_dq) / PEAK_BF16_TFLOPS, 4),
-                        "traffic": MEASURED_TRAFFIC.get(w.name, {}).get("attn_bwd_dq_kernel")},
-        "roofline_fwd": {"kernel": "attn_fwd_kernel", "bound": "mfma", "achieved": round(tf(f_fwd, ms_fwd), 1),
+                        "traffic": MEASURED_TRAFFIC.get(w.name, {}).get(dq_name)},
+        "roofline_fwd": {"kernel": fwd_name, "bound": "mfma", "achieved": round(tf(f_fwd, ms_fwd), 1),
                          "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                          "frac": round(tf(f_fwd, ms_fwd) / PEAK_BF16_TFLOPS, 4),
-                         "traffic": MEASURED_TRAFFIC.get(w.name, {}).get("attn_fwd_kernel")},
+                         "traffic": MEASURED_TRAFFIC.get(w.name, {}).get(fwd_name)},
         "context": PAPER_CONTEXT,
     }
     if not args.no_cpu_baseline:

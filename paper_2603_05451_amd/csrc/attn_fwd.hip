@@ -45,6 +45,11 @@ constexpr int FWD_NT = 256;
 #define ATTN_VARLEN 1
 #include "attn_fwd_kernel.inc"
 #undef ATTN_VARLEN
+#define ATTN_VARLEN 0
+#define ATTN_FWD_WIDE 1
+#include "attn_fwd_kernel.inc"
+#undef ATTN_FWD_WIDE
+#undef ATTN_VARLEN
 #include "attn_fwd_launch.inc"
 
 // ---- fp16 kernels: the same text, element type _Float16 (v_mfma_f32_32x32x16_f16)
@@ -61,6 +66,11 @@ namespace f16k {
 #undef ATTN_VARLEN
 #define ATTN_VARLEN 1
 #include "attn_fwd_kernel.inc"
+#undef ATTN_VARLEN
+#define ATTN_VARLEN 0
+#define ATTN_FWD_WIDE 1
+#include "attn_fwd_kernel.inc"
+#undef ATTN_FWD_WIDE
 #undef ATTN_VARLEN
 #include "attn_fwd_launch.inc"
 }  // namespace f16k
