@@ -227,8 +227,8 @@ def main():
     dkdv_name = "attn_bwd_dkdv_ws_kernel" if w.dqk == 128 else "attn_bwd_dkdv_kernel"
     # at d = 128 and N % 256 == 0 the library runs its 256-query blocks (forward always, dQ without a mask)
     wide = w.dqk == 128 and w.N % 256 == 0
-    fwd_name = "attn_fwd_wide_kernel" if wide else "attn_fwd_kernel"
-    dq_name = "attn_bwd_dq_wide_kernel" if wide and not w.causal else "attn_bwd_dq_kernel"
+    fwd_name = "attn_fwd_wide_kernel" if wide and w.N >= (8192 if w.causal else 2048) else "attn_fwd_kernel"
+    dq_name = "attn_bwd_dq_wide_kernel" if wide and not w.causal and w.N >= 4096 else "attn_bwd_dq_kernel"
     out = {
         "metric": "attention fwd / bwd TFLOPs/s (bf16) and % of MI355X dense BF16 MFMA peak",
         "value": round(tf(f_fwd + f_bwd, ms_step), 2), "unit": "TFLOP/s",

@@ -64,13 +64,14 @@ def test_varlen_fwd_parity(oracle, name, lengths, H, Hkv, dqk, dv, causal, seed)
         assert err <= LSE_ABS, f"varlen LSE {name} seq{b} len{n}: {err:.3e}"
 
 
-@pytest.mark.parametrize("N,causal", [(384, True), (512, True), (768, False)])
-def test_varlen_fwd_equals_fixed_length_bitwise(N, causal):
+@pytest.mark.parametrize("B,N,causal", [(3, 384, True), (2, 2048, False), (1, 8192, True)])
+def test_varlen_fwd_equals_fixed_length_bitwise(B, N, causal):
     """Equal lengths that are multiples of 128: the packed call must reproduce attn_fwd bit for bit
-    (same tiles, same order of operations per wave).  At N = 512 and 768 attn_fwd runs its 256-query
-    blocks, the packed call 128-query ones: every wave still does the same arithmetic."""
+    (same tiles, same order of operations per wave).  At N = 2048 without a mask and N = 8192 with
+    the causal mask attn_fwd runs its 256-query blocks, the packed call 128-query ones: every wave
+    still does the same arithmetic."""
     import paper_2603_05451_amd as A
-    w = I.Workload("eq", 3, 4, 2, N, 128, 128, causal, 41)
+    w = I.Workload("eq", B, 4, 2, N, 128, 128, causal, 41)
     x = I.make_inputs(w, with_do=False)
     q, k, v = (x[n].cuda() for n in ("q", "k", "v"))
     o, lse = A.attn_fwd(q, k, v, w.scale, w.causal)
@@ -118,8 +119,8 @@ def test_varlen_bwd_matches_fixed_length_and_is_reproducible():
     tiles, so dQ, dK and dV are bit-identical to attn_bwd; two packed calls give identical bits."""
     import paper_2603_05451_amd as A
     for dqk, dv_, seed, N, causal in ((128, 128, 42, 384, True), (64, 64, 43, 384, True), (192, 128, 44, 384, True),
-                                      (128, 128, 45, 512, False), (128, 128, 46, 512, True)):   # 512: 256-query blocks
-        w = I.Workload("eq", 2, 4, 2, N, dqk, dv_, causal, seed)
+                                      (128, 128, 45, 4096, False)):   # N = 4096 unmasked: 256-query dQ blocks
+        w = I.Workload("eq", 2 if N < 1024 else 1, 4, 2, N, dqk, dv_, causal, seed)
         x = I.make_inputs(w)
         q, k, v, do = (x[n].cuda() for n in ("q", "k", "v", "do"))
         o, lse = A.attn_fwd(q, k, v, w.scale, w.causal)
