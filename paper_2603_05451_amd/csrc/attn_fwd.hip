@@ -10,6 +10,8 @@
 //   wave w = 32 query rows; it keeps its Q rows in registers for the whole kernel;
 //   K/V tiles of BN = 64 keys stream through LDS, double buffered, copied straight
 //   from global memory into LDS (no VGPR staging) one tile ahead of the compute.
+//   At d = 128 and long sequences a second form of the same kernel text runs instead: 8 waves
+//   = 256 queries per block (attn_fwd_wide_kernel), each K/V tile copied once per 256 queries.
 //
 // MFMA orientation.  Scores are computed TRANSPOSED, S^T = K Q^T (keys on the MFMA row
 // axis, queries on the column axis).  In the 32x32 accumulator layout a lane then owns

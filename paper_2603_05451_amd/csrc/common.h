@@ -124,32 +124,13 @@ __device__ __forceinline__ void dma4(const void* gsrc, ATTN_LDS char* lds_base) 
                  :: "s"(m0), "v"(gsrc) : "memory");
 }
 
-// Asynchronous copy of a ROWS x D bf16 tile from global memory (row stride `gstride`
-// elements) into an LDS tile, by all NT threads of the block.  No VGPR staging: each
-// wave instruction moves 64 x 16 bytes straight into LDS.  Completion is observed with
-// wait_async_copies() followed by a workgroup barrier.
-template <int ROWS, int D, int NT>
-__device__ __forceinline__ void tile_load_async(const bf16* __restrict__ g, int64_t gstride,
-                                                ATTN_LDS char* lds, int tid)
-{
-    constexpr int CPR = D / 8;
-    constexpr int NCHUNK = ROWS * CPR;
-    static_assert(NCHUNK % NT == 0, "tile must be a whole number of block-wide copies");
-    const int wave = tid >> 6, lane = tid & 63;
-#pragma unroll
-    for (int t = 0; t < NCHUNK / NT; ++t) {
-        const int p0 = (t * (NT / 64) + wave) * 64;   // first chunk this wave instruction writes
-        const int p = p0 + lane;
-        const int row = p / CPR;
-        const int chunk = swz_chunk<D>(row, p % CPR);   // XOR is its own inverse
-        dma16(g + (int64_t)row * gstride + chunk * 8, lds + p0 * 16);
-    }
-}
-
-// Tile copy for the main loops.  The per-lane byte offsets inside a tile and the wave's LDS
-// slice offsets are computed once (init); a tile is then copied with N wave instructions that
-// take the tile's global base address in SGPRs (advanced with scalar arithmetic per tile) and
-// the lane offset in one VGPR: no vector ALU work per tile.
+// Tile copy for the main loops: ROWS x D 16-bit elements from global memory (row stride given in
+// elements) into an LDS tile, by all NT threads of the block, without VGPR staging: each wave
+// instruction moves 64 x 16 bytes straight into LDS.  Completion is observed with
+// wait_async_copies() followed by a workgroup barrier.  The per-lane byte offsets inside a tile
+// and the wave's LDS slice offsets are computed once (init); a tile is then copied with N wave
+// instructions that take the tile's global base address in SGPRs (advanced with scalar
+// arithmetic per tile) and the lane offset in one VGPR: no vector ALU work per tile.
 template <int ROWS, int D, int NT>
 struct TileCopy {
     static constexpr int N = ROWS * (D / 8) / NT;   // wave instructions per thread and tile
