@@ -219,6 +219,15 @@ long long attn_exp2_rate(float* out, int degree, int iters, void* stream);
 enum { ATTN_MFMA_RATE_BLOCKS = 256 };
 long long attn_mfma_rate(float* out, int random_operands, int iters, void* stream);
 
+/* LDS read rate in the kernels' two access patterns, to put their LDS traffic in proportion:
+ * enqueues ATTN_LDS_RATE_BLOCKS blocks of 256 threads (2 resident per CU) that read a swizzled
+ * 64 x 128 tile of 16-bit elements over and over, pattern 0 with ds_read_b128 as the MFMA
+ * A-operand fragments are read, pattern 1 with ds_read_b64_tr_b16 as the transposed fragments
+ * are; writes one float per thread to out (device, ATTN_LDS_RATE_BLOCKS * 256 floats) and
+ * returns the number of bytes read from LDS (> 0), or a negative error code. */
+#define ATTN_LDS_RATE_BLOCKS 512
+long long attn_lds_rate(float* out, int pattern, int iters, void* stream);
+
 /* Human-readable text for a return code (static storage). */
 const char* attn_strerror(int code);
 

@@ -74,6 +74,8 @@ def lib():
         L.attn_exp2_emulated.restype = i
         L.attn_exp2_rate.argtypes = [vp, i, i, vp]
         L.attn_exp2_rate.restype = ctypes.c_longlong
+        L.attn_lds_rate.argtypes = [vp, i, i, vp]
+        L.attn_lds_rate.restype = ctypes.c_longlong
         L.attn_mfma_rate.argtypes = [vp, i, i, vp]
         L.attn_mfma_rate.restype = ctypes.c_longlong
         L.attn_strerror.argtypes = [i]
@@ -349,6 +351,21 @@ def attn_mfma_rate(random_operands, iters, out=None, stream=None):
         out = torch.empty(ATTN_MFMA_RATE_BLOCKS * 512, dtype=torch.float32, device="cuda")
     n = lib().attn_mfma_rate(ctypes.c_void_p(out.data_ptr()), int(bool(random_operands)), int(iters),
                              _stream(stream))
+    if n <= 0:
+        _check(int(n) or ATTN_EINVAL)
+    return int(n), out
+
+
+ATTN_LDS_RATE_BLOCKS = 512
+
+
+def attn_lds_rate(pattern, iters, out=None, stream=None):
+    """Enqueue the LDS read-rate kernel (pattern 0: ds_read_b128 A-operand fragments, 1: transposing
+    reads); returns (bytes read from LDS, out tensor)."""
+    import torch
+    if out is None:
+        out = torch.empty(ATTN_LDS_RATE_BLOCKS * 256, dtype=torch.float32, device="cuda")
+    n = lib().attn_lds_rate(ctypes.c_void_p(out.data_ptr()), int(pattern), int(iters), _stream(stream))
     if n <= 0:
         _check(int(n) or ATTN_EINVAL)
     return int(n), out

@@ -8,6 +8,7 @@
 // field and added to the polynomial's bits.  Coefficients: minimax relative error on [0, 1),
 // from gen_exp2_coeffs.py (Remez exchange); the section prints none.
 #include "../../include/attn.h"
+#include "common.h"
 #include "launch.h"
 
 #include <hip/hip_runtime.h>
@@ -107,9 +108,65 @@ __global__ void __launch_bounds__(512) mfma_rate_kernel(float* __restrict__ out,
     out[(size_t)blockIdx.x * 512 + threadIdx.x] = c[0][0] + c[1][1] + c[2][2] + c[3][3];
 }
 
+// LDS read rate in the two access patterns of the attention kernels, on a swizzled 64 x 128 tile
+// of 16-bit elements: PATTERN 0 = ds_read_b128 of MFMA A-operand fragments (K, Q, dO: lane =
+// tile row c, 16-byte chunk 2*ks + h), PATTERN 1 = ds_read_b64_tr_b16 of transposed fragments
+// (V^T, K^T, Q^T, dO^T).  Eight reads are kept in flight per wave; the data are never used for
+// arithmetic.  256 threads per block, 2 blocks per CU resident (32 KiB of LDS each).
+template <int PATTERN>
+__global__ void __launch_bounds__(256, 2) lds_rate_kernel(float* __restrict__ out, int iters)
+{
+    __shared__ __attribute__((aligned(1024))) char tile[4][8192];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    for (int i = tid; i < 4 * 8192 / 4; i += 256) ((float*)tile)[i] = (float)i;
+    __syncthreads();
+    const ATTN_LDS char* base = (const ATTN_LDS char*)&tile[0][0] + (wave & 1) * 16384;
+    const int h = lane >> 5, c = lane & 31, i16 = lane & 15;
+    const ATTN_LDS char* p[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+        if (PATTERN == 0) {
+            p[u] = base + tile_off<128>(c, 2 * u + h);
+        } else {
+            const int kk = u >> 2, db = u & 3;
+            p[u] = base + tile_off<128>(16 * kk + 4 * h + (i16 >> 2), 4 * db + 2 * ((lane >> 4) & 1) + ((i16 & 3) >> 1)) +
+                   (i16 & 1) * 8;
+        }
+    }
+    float acc = 0.f;
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            if (PATTERN == 0) {
+                f32x4 v;
+                asm volatile("ds_read_b128 %0, %1\n\ts_waitcnt lgkmcnt(7)" : "=v"(v) : "v"(p[u]) : "memory");
+                acc += v[0];
+            } else {
+                float2 v;
+                asm volatile("ds_read_b64_tr_b16 %0, %1\n\ts_waitcnt lgkmcnt(7)" : "=v"(v) : "v"(p[u]) : "memory");
+                acc += v.x;
+            }
+        }
+    }
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    out[(size_t)blockIdx.x * 256 + tid] = acc;
+}
+
 }  // namespace attn
 
 extern "C" {
+
+long long attn_lds_rate(float* out, int pattern, int iters, void* stream)
+{
+    using namespace attn;
+    if (!out || iters <= 0) return ATTN_EINVAL;
+    hipError_t e;
+    if (pattern == 0) e = launch_kernel(lds_rate_kernel<0>, dim3(ATTN_LDS_RATE_BLOCKS), dim3(256), 0, stream, out, iters);
+    else if (pattern == 1) e = launch_kernel(lds_rate_kernel<1>, dim3(ATTN_LDS_RATE_BLOCKS), dim3(256), 0, stream, out, iters);
+    else return ATTN_EUNSUPPORTED;
+    if (e != hipSuccess) return ATTN_ELAUNCH;
+    return (long long)ATTN_LDS_RATE_BLOCKS * 4 * iters * 8 * (pattern == 0 ? 1024 : 512);
+}
 
 long long attn_mfma_rate(float* out, int random_operands, int iters, void* stream)
 {

@@ -96,3 +96,26 @@ def test_matrix_core_ceiling_on_random_operands():
     with open(path, "w") as f:
         f.write("\n".join(f"{k} operands : {v:.0f} TFLOP/s" for k, v in rates.items()) + "\n")
     assert 1000 < rates["N(0,1)"] <= rates["constant"] * 1.02 < 2600
+
+
+def test_lds_read_rate_in_the_kernels_access_patterns():
+    """Bytes per clock and CU that the LDS delivers in the two read patterns of the attention
+    kernels (swizzled tiles: no bank conflicts expected).  The forward kernel reads 32 KiB per
+    wave and 64-key tile, i.e. about 55 bytes per clock and CU at its measured speed."""
+    import paper_2603_05451_amd as A
+    rates = {}
+    for name, pat in (("ds_read_b128, A-operand fragments", 0), ("ds_read_b64_tr_b16, transposed fragments", 1)):
+        A.attn_lds_rate(pat, 200)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        nbytes, out = A.attn_lds_rate(pat, 20000)
+        e1.record()
+        e1.synchronize()
+        assert torch.isfinite(out).all()
+        rates[name] = nbytes / (e0.elapsed_time(e1) * 1e-3) / 256 / 2.4e9      # bytes per clock and CU at 2.4 GHz
+    print("LDS bytes / clock / CU:", {k: round(v) for k, v in rates.items()})
+    path = os.path.join(os.path.dirname(os.path.dirname(__file__)), "gpurun_out", "lds_rates.txt")
+    os.makedirs(os.path.dirname(path), exist_ok=True)
+    with open(path, "w") as f:
+        f.write("\n".join(f"{k} : {v:.0f} B/clk/CU (at 2.4 GHz)" for k, v in rates.items()) + "\n")
+    assert all(100 < v < 300 for v in rates.values())
