@@ -1,0 +1,43 @@
+"""Tensors of more than 2^31 elements (4.4 GB each): element and byte offsets beyond 32 bits in
+every kernel.  Inputs are drawn on the GPU (seeded); the oracle checks sampled query rows and the
+last keys of the first and of the last (batch, head), whose data sit at the two ends of the
+tensors."""
+import numpy as np
+import pytest
+import torch
+
+from parity import LSE_ABS, assert_close, assert_close_wide
+
+pytestmark = pytest.mark.gpu
+
+
+def test_offsets_beyond_32_bits(oracle):
+    import paper_2603_05451_amd as A
+    B, N, H, d = 33, 16384, 32, 128
+    assert B * N * H * d > 2 ** 31
+    if torch.cuda.mem_get_info()[0] < 60 * 2 ** 30:
+        pytest.skip("needs about 40 GB of free device memory")
+    g = torch.Generator(device="cuda").manual_seed(1234)
+    draw = lambda: torch.randn((B, N, H, d), generator=g, device="cuda", dtype=torch.bfloat16)
+    q, k, v, do = draw(), draw(), draw(), draw()
+    scale, causal = 1.0 / np.sqrt(d), True
+    o, lse = A.attn_fwd(q, k, v, scale, causal)
+    dq, dk, dv = A.attn_bwd(q, k, v, o, do, lse, scale, causal)
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(7)
+    for b, h in ((0, 0), (B - 1, H - 1), (B // 2, 5)):
+        rows = np.unique(np.concatenate([[0, 127, 128, N - 1], rng.integers(0, N, 12), np.arange(N - 128, N)]))
+        f = lambda t, r=slice(None): t[b, r, h].double().cpu().numpy()[None, :, None, :]
+        ridx = torch.from_numpy(rows).cuda()
+        fq, fdo = f(q, ridx), f(do, ridx)
+        fk, fv = f(k), f(v)
+        ro, rlse = oracle.attn_fwd(fq, fk, fv, scale, causal, q_pos=rows)
+        rdq, rdk, rdv = oracle.attn_bwd(fq, fk, fv, fdo, scale, causal, q_pos=rows)
+        tag = f"b{b} h{h}"
+        assert_close(f(o, ridx), ro, "large O " + tag)
+        assert np.abs(lse[b, h, ridx].cpu().numpy()[None, None] - rlse).max() <= LSE_ABS
+        assert_close(f(dq, ridx), rdq, "large dQ " + tag)
+        # under the causal mask only the last 128 queries reach the last 128 keys: complete sums
+        last = slice(N - 128, N)
+        assert_close_wide(f(dk, last), rdk[:, N - 128:], "large dK " + tag)
+        assert_close_wide(f(dv, last), rdv[:, N - 128:], "large dV " + tag)
