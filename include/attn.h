@@ -133,7 +133,10 @@ int attn_varlen_fwd(const void* q, const void* k, const void* v, void* o, float*
  * then pass cu_seqlens_q = cu_seqlens_k = NULL: it skips the plan kernel and uses the tables as
  * they are (a backward call needs tables written by this function or by an earlier backward call;
  * a forward call with non-NULL cu_seqlens writes the query table only).  Calls never modify the
- * tables otherwise; results are bit-identical to those of calls that rebuild them. */
+ * tables otherwise; results are bit-identical to those of calls that rebuild them.  Table entries
+ * carry a mark and are checked against total_q: on a workspace that was never planned the kernels
+ * find nothing to act on and leave the outputs untouched (tables planned for OTHER lengths with
+ * the same totals cannot be told apart: that remains the caller's responsibility). */
 int attn_varlen_plan(const int* cu_seqlens_q, const int* cu_seqlens_k, int B, int total_q, int total_k,
                      int H, int Hkv, int d_qk, int d_v, void* workspace, size_t workspace_bytes, void* stream);
 /* Backward of attn_varlen_fwd (paper Sec. 2.1 second display, per sequence): o and lse must be that

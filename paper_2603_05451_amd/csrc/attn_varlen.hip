@@ -6,7 +6,7 @@
 // cu_k[b] .. cu_k[b+1]-1 (cu_k may be the same array: self-attention).
 // Output: two tables, one entry per 128-row QUERY tile and one per 128-row KEY tile.  An entry is
 // two int4: {first query row, query length, first key row, key length} of the sequence and
-// {tile index inside the sequence, 1, sequence index, 0}.  Sequences are ordered by the length of the loop one
+// {tile index inside the sequence, kPlanUsed, sequence index, 0}.  Sequences are ordered by the length of the loop one
 // of their tiles runs -- the key tile count for query tiles, the query tile count for key tiles --
 // longest first (a counting sort over tile counts; ties keep no particular order, which does not
 // matter because no result depends on which block computes which tile), and inside a sequence
@@ -44,7 +44,7 @@ __device__ void plan_build(const int* __restrict__ cu_q, const int* __restrict__
             const int nt = own_tiles(ql, kl);
             for (int t = 0; t < nt && run < max_tiles; ++t, ++run) {
                 plan[2 * run] = make_int4(qs, ql, ks, kl);
-                plan[2 * run + 1] = make_int4(nt - 1 - t, 1, b, 0);
+                plan[2 * run + 1] = make_int4(nt - 1 - t, kPlanUsed, b, 0);
             }
         }
     }
@@ -89,7 +89,7 @@ __device__ void plan_build(const int* __restrict__ cu_q, const int* __restrict__
         for (int t = 0; t < nt; ++t)
             if (first + t < max_tiles) {
                 plan[2 * (first + t)] = make_int4(qs, ql, ks, kl);
-                plan[2 * (first + t) + 1] = make_int4(nt - 1 - t, 1, b, 0);
+                plan[2 * (first + t) + 1] = make_int4(nt - 1 - t, kPlanUsed, b, 0);
             }
     }
     __syncthreads();

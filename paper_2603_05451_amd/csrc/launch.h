@@ -18,6 +18,10 @@ struct VarlenStrides {
     long long lse_batch, lse_head;      // lse index = t + s * lse_batch + h * lse_head
 };
 
+// Mark of a used entry of the tile tables.  Not 1: a workspace that was never planned, or whose
+// tables were overwritten, then holds no entry that a kernel would act on.
+constexpr int kPlanUsed = 0x5A17AB1E;
+
 struct FwdArgs {
     const void *q, *k, *v;
     void* o;

@@ -221,7 +221,7 @@ def check_table(table, want, loop_tiles, index_of):
     tile of that sequence runs; index_of: (q start, q len, k start, k len) -> sequence index.  Every
     wanted tile once, longest loops first, a sequence's tiles contiguous and from last to first, the
     rest of the table zero."""
-    used = table[table[:, 5] == 1]
+    used = table[table[:, 5] == 0x5A17AB1E]
     assert len(used) == len(want) and {tuple(int(x) for x in e[:5]) for e in used} == want
     assert (table[len(used):] == 0).all() and (used[:, 7] == 0).all()
     assert all(int(e[6]) == index_of[tuple(int(x) for x in e[:4])] for e in used)
@@ -378,3 +378,22 @@ def test_cached_plan_tables_give_identical_results():
         torch.cuda.synchronize()
         assert torch.equal(o2, o) and torch.equal(lse2, lse)
         assert all(torch.equal(a, b) for a, b in zip(got, ref))
+
+
+def test_unplanned_workspace_is_not_acted_on():
+    """Calls without cu_seqlens on a workspace whose tables were never built (zeros, or bytes that
+    do not carry the entry mark): the kernels find no entry to act on and leave the outputs alone."""
+    import paper_2603_05451_amd as A
+    H, Hkv, d, B, T = 2, 1, 64, 3, 700
+    x, cu, scale = packed_inputs([300, 150, 250], H, Hkv, d, d, 73, with_do=True)
+    q, k, v, do = (x[n].cuda() for n in ("q", "k", "v", "do"))
+    need = A.attn_varlen_workspace_bytes(B, T, T, H, Hkv, d, d, True)
+    for fill in (0, 0x11):
+        ws = torch.full((need,), fill, dtype=torch.uint8, device="cuda")
+        o = torch.full((T, H, d), 7.0, dtype=torch.bfloat16, device="cuda")
+        lse = torch.full((H, T), 7.0, dtype=torch.float32, device="cuda")
+        A.attn_varlen_fwd(q, k, v, None, scale, True, o=o, lse=lse, workspace=ws, B=B)
+        g = [torch.full_like(t, 7.0) for t in (q, k, v)]
+        A.attn_varlen_bwd(q, k, v, o, do, lse, None, scale, True, dq=g[0], dk=g[1], dv=g[2], workspace=ws, B=B)
+        torch.cuda.synchronize()
+        assert (o == 7.0).all() and (lse == 7.0).all() and all((t == 7.0).all() for t in g)
