@@ -2,7 +2,10 @@
 from __future__ import annotations
 
 import os
+import shutil
 import subprocess
+import tempfile
+from concurrent.futures import ThreadPoolExecutor
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
@@ -10,21 +13,35 @@ LIB = os.path.join(HERE, "libattn.so")
 SOURCES = ["attn_api.hip", "attn_fwd.hip", "attn_bwd.hip", "attn_varlen.hip", "exp2_probe.hip"]
 # packed-fp32 instruction selection is switched off on purpose (device passes only; the
 # host pass prints a harmless "not a recognized feature" note).
-HIPCC_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
+HIPCC_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
                "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
                "-Wno-unused-command-line-argument"]
 
 
-def build_library(verbose: bool = False) -> str:
-    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    cmd = [hipcc, *HIPCC_FLAGS, "-o", LIB, *[os.path.join(CSRC, s) for s in SOURCES]]
+def _run(cmd, verbose):
     res = subprocess.run(cmd, capture_output=True, text=True)
     if verbose or res.returncode != 0:
         keep = [ln for ln in (res.stdout + res.stderr).splitlines() if "packed-fp32-ops" not in ln]
         if keep:
             print("\n".join(keep))
     if res.returncode != 0:
-        raise RuntimeError("hipcc failed building libattn.so")
+        raise RuntimeError("hipcc failed building libattn.so: " + " ".join(cmd[-3:]))
+
+
+def build_library(verbose: bool = False) -> str:
+    """One hipcc process per source file (the two attention files dominate: every kernel body is
+    instantiated per head dim, mask, mode and element type), then one link step."""
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    tmp = tempfile.mkdtemp(prefix="libattn_build_")
+    try:
+        objs = [os.path.join(tmp, s.replace(".hip", ".o")) for s in SOURCES]
+        jobs = [[hipcc, *HIPCC_FLAGS, "-c", os.path.join(CSRC, s), "-o", o] for s, o in zip(SOURCES, objs)]
+        with ThreadPoolExecutor(max_workers=min(len(jobs), os.cpu_count() or 1, 8)) as pool:
+            list(pool.map(lambda c: _run(c, verbose), jobs))
+        _run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB + ".tmp", *objs], verbose)
+        os.replace(LIB + ".tmp", LIB)
+    finally:
+        shutil.rmtree(tmp, ignore_errors=True)
     return LIB
 
 
