@@ -161,6 +161,9 @@ def main():
                     help="also time every workload of the task's config list and write a markdown table to FILE")
     ap.add_argument("--varlen-table", metavar="FILE", default=None,
                     help="time the variable-length workloads instead, write a markdown table, print nothing else")
+    ap.add_argument("--zero-inputs", action="store_true",
+                    help="measurement of the power limit only: time the same kernels on all-zero q, k, v, dO "
+                         "(same instruction stream, no operand toggling); the line says so in its data field")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one 1 GiB device-to-device copy (reference for rocprofv3 FETCH_SIZE/WRITE_SIZE)")
     args = ap.parse_args()
@@ -182,6 +185,8 @@ def main():
     named["target"] = I.TARGET
     w = named[args.workload]
     x = I.make_inputs(w)
+    if args.zero_inputs:
+        x = {n: torch.zeros_like(t) for n, t in x.items()}
     q, k, v, do = (x[n].cuda() for n in ("q", "k", "v", "do"))
     o = torch.empty((w.B, w.N, w.H, w.dv), dtype=torch.bfloat16, device="cuda")
     lse = torch.empty((w.B, w.H, w.N), dtype=torch.float32, device="cuda")
@@ -234,7 +239,8 @@ def main():
         "value": round(tf(f_fwd + f_bwd, ms_step), 2), "unit": "TFLOP/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_step, 4),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "bf16", "data": "synthetic N(0,1) q,k,v,dO, seeded, resident in HBM",
+        "dtype": "bf16", "data": ("ALL-ZERO q,k,v,dO (power-limit measurement, not the workload)" if args.zero_inputs
+                                  else "synthetic N(0,1) q,k,v,dO, seeded, resident in HBM"),
         "config": {"workload": f"{w.name}: B={w.B} H={w.H} Hkv={w.Hkv} N={w.N} d_qk={w.dqk} d_v={w.dv} "
                                f"causal={w.causal}, step = attn_fwd + attn_bwd",
                    "flops_convention": "fwd 2 N^2 (d_qk+d_v) H B (halved if causal), bwd 2.5x fwd"},
