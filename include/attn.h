@@ -174,30 +174,36 @@ int attn_varlen_bwd_dtype(int dtype, const void* q, const void* k, const void* v
 
 /* Strided layouts: the same attention on equal-length batches whose tensors are views with
  * arbitrary batch, token and head strides -- [B, H, N, d] tensors, slices of a fused QKV
- * projection, padded buffers -- and any N >= 1 (no multiple-of-128 requirement).  The head dim is
- * contiguous.  Element (b, n, h, c) of a tensor x with strides sx (counted in ELEMENTS) is
- * x[b * sx->batch + n * sx->row + h * sx->head + c]; q, o, d_o, dq have H heads, k, v, dk, dv Hkv.
+ * projection, padded buffers -- with Nq >= 1 queries and Nk >= 1 keys per sequence (no
+ * multiple-of-128 requirement; Nq != Nk is a prefix held in a cache, a decode step or
+ * cross-attention).  The head dim is contiguous.  Element (b, n, h, c) of a tensor x with strides
+ * sx (counted in ELEMENTS) is x[b * sx->batch + n * sx->row + h * sx->head + c]; q, o, d_o, dq
+ * have Nq tokens and H heads, k, v, dk, dv Nk tokens and Hkv heads.
  * Every stride must be a non-negative multiple of 8 (16-byte vector accesses), non-zero
- * wherever the corresponding extent exceeds 1, and the token stride at most 2^23 elements; outputs must not overlap themselves or any input.
- * lse is [B, H, N] fp32, contiguous.  Runs the variable-length kernels on the sequence
- * boundaries {0, N, 2N, ...} generated on the device; on contiguous [B, N, H, d] tensors with N a
- * multiple of 128 the results are bit-identical to attn_fwd_ex / attn_bwd_ex.
+ * wherever the corresponding extent exceeds 1, and the token stride at most 2^23 elements;
+ * outputs must not overlap themselves or any input.  lse is [B, H, Nq] fp32, contiguous.
+ * causal != 0: the last query is aligned with the last key, key j is visible to query i iff
+ * j <= i + Nk - Nq (the convention of the variable-length calls; the paper is silent on
+ * Nq != Nk), and Nk >= Nq is required (ATTN_EINVAL otherwise).
+ * Runs the variable-length kernels on the sequence boundaries {0, Nq, 2 Nq, ...} and
+ * {0, Nk, 2 Nk, ...} generated on the device; on contiguous [B, N, H, d] tensors with
+ * Nq = Nk = N a multiple of 128 the results are bit-identical to attn_fwd_ex / attn_bwd_ex.
  *   workspace: attn_strided_workspace_bytes(..., backward) bytes, 256-byte aligned, contents
  *   ignored on entry.  Other conventions as in attn_fwd_dtype / attn_bwd_dtype. */
 typedef struct attn_strides {
     long long batch, row, head;
 } attn_strides_t;
-size_t attn_strided_workspace_bytes(int B, int H, int Hkv, int N, int d_qk, int d_v, int backward);
+size_t attn_strided_workspace_bytes(int B, int H, int Hkv, int Nq, int Nk, int d_qk, int d_v, int backward);
 int attn_fwd_strided(int dtype, const void* q, const attn_strides_t* sq, const void* k, const attn_strides_t* sk,
                      const void* v, const attn_strides_t* sv, void* o, const attn_strides_t* so, float* lse,
-                     int B, int H, int Hkv, int N, int d_qk, int d_v, float scale, int causal,
+                     int B, int H, int Hkv, int Nq, int Nk, int d_qk, int d_v, float scale, int causal,
                      void* workspace, size_t workspace_bytes, void* stream);
 int attn_bwd_strided(int dtype, const void* q, const attn_strides_t* sq, const void* k, const attn_strides_t* sk,
                      const void* v, const attn_strides_t* sv, const void* o, const attn_strides_t* so,
                      const void* d_o, const attn_strides_t* sdo, const float* lse,
                      void* dq, const attn_strides_t* sdq, void* dk, const attn_strides_t* sdk,
                      void* dv, const attn_strides_t* sdv,
-                     int B, int H, int Hkv, int N, int d_qk, int d_v, float scale, int causal,
+                     int B, int H, int Hkv, int Nq, int Nk, int d_qk, int d_v, float scale, int causal,
                      void* workspace, size_t workspace_bytes, void* stream);
 
 /* Software 2^x of paper Sec. 3.1.3 (range reduction + degree-n minimax polynomial, p0 = 1, Horner

@@ -58,11 +58,11 @@ def lib():
         L.attn_varlen_workspace_bytes.argtypes = [i] * 8
         L.attn_varlen_workspace_bytes.restype = sz
         sp = ctypes.POINTER(AttnStrides)
-        L.attn_strided_workspace_bytes.argtypes = [i] * 7
+        L.attn_strided_workspace_bytes.argtypes = [i] * 8
         L.attn_strided_workspace_bytes.restype = sz
-        L.attn_fwd_strided.argtypes = [i] + [vp, sp] * 4 + [vp] + [i] * 6 + [f, i, vp, sz, vp]
+        L.attn_fwd_strided.argtypes = [i] + [vp, sp] * 4 + [vp] + [i] * 7 + [f, i, vp, sz, vp]
         L.attn_fwd_strided.restype = i
-        L.attn_bwd_strided.argtypes = [i] + [vp, sp] * 5 + [vp] + [vp, sp] * 3 + [i] * 6 + [f, i, vp, sz, vp]
+        L.attn_bwd_strided.argtypes = [i] + [vp, sp] * 5 + [vp] + [vp, sp] * 3 + [i] * 7 + [f, i, vp, sz, vp]
         L.attn_bwd_strided.restype = i
         L.attn_varlen_plan.argtypes = [vp, vp] + [i] * 7 + [vp, sz, vp]
         L.attn_varlen_plan.restype = i
@@ -262,29 +262,30 @@ def _view(t, name, shape, like):
     return ctypes.c_void_p(t.data_ptr()), ctypes.byref(AttnStrides(t.stride(0), t.stride(1), t.stride(2)))
 
 
-def attn_strided_workspace_bytes(B, H, Hkv, N, d_qk, d_v, backward) -> int:
-    return int(lib().attn_strided_workspace_bytes(B, H, Hkv, N, d_qk, d_v, int(bool(backward))))
+def attn_strided_workspace_bytes(B, H, Hkv, Nq, Nk, d_qk, d_v, backward) -> int:
+    return int(lib().attn_strided_workspace_bytes(B, H, Hkv, Nq, Nk, d_qk, d_v, int(bool(backward))))
 
 
 def attn_fwd_strided(q, k, v, scale, causal, o=None, lse=None, workspace=None, stream=None):
-    """attn_fwd on views: q [B,N,H,d_qk], k [B,N,Hkv,d_qk], v [B,N,Hkv,d_v] of any strides (the last
-    axis contiguous), e.g. x.permute(0, 2, 1, 3) of a [B,H,N,d] tensor; any N >= 1.  o may be a view
-    too (default: a new contiguous [B,N,H,d_v]); lse [B,H,N] fp32 contiguous."""
+    """attn_fwd on views: q [B,Nq,H,d_qk], k [B,Nk,Hkv,d_qk], v [B,Nk,Hkv,d_v] of any strides (the
+    last axis contiguous), e.g. x.permute(0, 2, 1, 3) of a [B,H,N,d] tensor; any Nq, Nk >= 1 (under a
+    causal mask the last query sees the last key, Nk >= Nq).  o may be a view too (default: a new
+    contiguous [B,Nq,H,d_v]); lse [B,H,Nq] fp32 contiguous."""
     import torch
     B, N, H, dqk = q.shape
-    Hkv, dv = k.shape[2], v.shape[3]
+    Nk, Hkv, dv = k.shape[1], k.shape[2], v.shape[3]
     if o is None:
         o = torch.empty((B, N, H, dv), dtype=q.dtype, device=q.device)
     if lse is None:
         lse = torch.empty((B, H, N), dtype=torch.float32, device=q.device)
     if not (lse.is_cuda and lse.dtype == torch.float32 and lse.is_contiguous() and tuple(lse.shape) == (B, H, N)):
-        raise ValueError("lse must be a contiguous fp32 CUDA tensor [B,H,N]")
-    need = attn_strided_workspace_bytes(B, H, Hkv, N, dqk, dv, False)
+        raise ValueError("lse must be a contiguous fp32 CUDA tensor [B,H,Nq]")
+    need = attn_strided_workspace_bytes(B, H, Hkv, N, Nk, dqk, dv, False)
     if workspace is None:
         workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=q.device)
-    rc = lib().attn_fwd_strided(_dtype_code(q), *_view(q, "q", (B, N, H, dqk), q), *_view(k, "k", (B, N, Hkv, dqk), q),
-                                *_view(v, "v", (B, N, Hkv, dv), q), *_view(o, "o", (B, N, H, dv), q),
-                                ctypes.c_void_p(lse.data_ptr()), B, H, Hkv, N, dqk, dv, float(scale),
+    rc = lib().attn_fwd_strided(_dtype_code(q), *_view(q, "q", (B, N, H, dqk), q), *_view(k, "k", (B, Nk, Hkv, dqk), q),
+                                *_view(v, "v", (B, Nk, Hkv, dv), q), *_view(o, "o", (B, N, H, dv), q),
+                                ctypes.c_void_p(lse.data_ptr()), B, H, Hkv, N, Nk, dqk, dv, float(scale),
                                 int(bool(causal)), ctypes.c_void_p(workspace.data_ptr()), workspace.numel(),
                                 _stream(stream))
     _check(rc)
@@ -293,23 +294,23 @@ def attn_fwd_strided(q, k, v, scale, causal, o=None, lse=None, workspace=None, s
 
 def attn_bwd_strided(q, k, v, o, d_o, lse, scale, causal, dq=None, dk=None, dv=None, workspace=None, stream=None):
     """Backward of attn_fwd_strided; every tensor may be a view.  Gradients default to new
-    contiguous [B,N,heads,d] tensors."""
+    contiguous tensors shaped like q, k and v."""
     import torch
     B, N, H, dqk = q.shape
-    Hkv, dv_ = k.shape[2], v.shape[3]
+    Nk, Hkv, dv_ = k.shape[1], k.shape[2], v.shape[3]
     dq = torch.empty((B, N, H, dqk), dtype=q.dtype, device=q.device) if dq is None else dq
-    dk = torch.empty((B, N, Hkv, dqk), dtype=q.dtype, device=q.device) if dk is None else dk
-    dv = torch.empty((B, N, Hkv, dv_), dtype=q.dtype, device=q.device) if dv is None else dv
+    dk = torch.empty((B, Nk, Hkv, dqk), dtype=q.dtype, device=q.device) if dk is None else dk
+    dv = torch.empty((B, Nk, Hkv, dv_), dtype=q.dtype, device=q.device) if dv is None else dv
     if not (lse.is_cuda and lse.dtype == torch.float32 and lse.is_contiguous() and tuple(lse.shape) == (B, H, N)):
-        raise ValueError("lse must be a contiguous fp32 CUDA tensor [B,H,N]")
-    need = attn_strided_workspace_bytes(B, H, Hkv, N, dqk, dv_, True)
+        raise ValueError("lse must be a contiguous fp32 CUDA tensor [B,H,Nq]")
+    need = attn_strided_workspace_bytes(B, H, Hkv, N, Nk, dqk, dv_, True)
     if workspace is None:
         workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=q.device)
-    rc = lib().attn_bwd_strided(_dtype_code(q), *_view(q, "q", (B, N, H, dqk), q), *_view(k, "k", (B, N, Hkv, dqk), q),
-                                *_view(v, "v", (B, N, Hkv, dv_), q), *_view(o, "o", (B, N, H, dv_), q),
+    rc = lib().attn_bwd_strided(_dtype_code(q), *_view(q, "q", (B, N, H, dqk), q), *_view(k, "k", (B, Nk, Hkv, dqk), q),
+                                *_view(v, "v", (B, Nk, Hkv, dv_), q), *_view(o, "o", (B, N, H, dv_), q),
                                 *_view(d_o, "d_o", (B, N, H, dv_), q), ctypes.c_void_p(lse.data_ptr()),
-                                *_view(dq, "dq", (B, N, H, dqk), q), *_view(dk, "dk", (B, N, Hkv, dqk), q),
-                                *_view(dv, "dv", (B, N, Hkv, dv_), q), B, H, Hkv, N, dqk, dv_, float(scale),
+                                *_view(dq, "dq", (B, N, H, dqk), q), *_view(dk, "dk", (B, Nk, Hkv, dqk), q),
+                                *_view(dv, "dv", (B, Nk, Hkv, dv_), q), B, H, Hkv, N, Nk, dqk, dv_, float(scale),
                                 int(bool(causal)), ctypes.c_void_p(workspace.data_ptr()), workspace.numel(),
                                 _stream(stream))
     _check(rc)

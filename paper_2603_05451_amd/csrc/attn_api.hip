@@ -320,18 +320,19 @@ int attn_varlen_bwd(const void* q, const void* k, const void* v, const void* o, 
 }
 
 // ---------------------------------------------------------------------------------------------
-// strided entry points: equal-length batches in any layout whose head dim is contiguous, run by
-// the variable-length kernels on a generated cu_seqlens = {0, N, 2N, ...}
+// strided entry points: equal-length batches (Nq queries and Nk keys per sequence) in any layout
+// whose head dim is contiguous, run by the variable-length kernels on generated boundaries
+// cu_seqlens_q = {0, Nq, 2 Nq, ...}, cu_seqlens_k = {0, Nk, 2 Nk, ...}
 
 namespace {
 
 size_t cu_bytes(int B) { return align_up((size_t)(B + 1) * sizeof(int), 256); }
 
-int check_strided(int B, int H, int Hkv, int N, int d_qk, int d_v)
+int check_strided(int B, int H, int Hkv, int Nq, int Nk, int d_qk, int d_v)
 {
-    if (B <= 0 || N <= 0) return ATTN_EINVAL;
-    if ((int64_t)B * N > 0x7fffffffLL) return ATTN_EUNSUPPORTED;
-    return check_varlen(B, B * N, B * N, H, Hkv, d_qk, d_v);
+    if (B <= 0 || Nq <= 0 || Nk <= 0) return ATTN_EINVAL;
+    if ((int64_t)B * Nq > 0x7fffffffLL || (int64_t)B * Nk > 0x7fffffffLL) return ATTN_EUNSUPPORTED;
+    return check_varlen(B, B * Nq, B * Nk, H, Hkv, d_qk, d_v);
 }
 
 // every stride a multiple of 8 elements (16 bytes: vector loads and the global->LDS copies),
@@ -353,40 +354,43 @@ attn::Stride3 as_packed(const attn_strides_t* s, int N)
 
 }  // namespace
 
-size_t attn_strided_workspace_bytes(int B, int H, int Hkv, int N, int d_qk, int d_v, int backward)
+size_t attn_strided_workspace_bytes(int B, int H, int Hkv, int Nq, int Nk, int d_qk, int d_v, int backward)
 {
-    if (check_strided(B, H, Hkv, N, d_qk, d_v) != ATTN_OK) return 0;
-    const VarlenLayout w = varlen_layout(B, B * N, B * N, H);
-    return cu_bytes(B) + (backward ? w.total_bwd : w.total_fwd);
+    if (check_strided(B, H, Hkv, Nq, Nk, d_qk, d_v) != ATTN_OK) return 0;
+    const VarlenLayout w = varlen_layout(B, B * Nq, B * Nk, H);
+    return 2 * cu_bytes(B) + (backward ? w.total_bwd : w.total_fwd);
 }
 
 int attn_fwd_strided(int dtype, const void* q, const attn_strides_t* sq, const void* k, const attn_strides_t* sk,
                      const void* v, const attn_strides_t* sv, void* o, const attn_strides_t* so, float* lse,
-                     int B, int H, int Hkv, int N, int d_qk, int d_v, float scale, int causal,
+                     int B, int H, int Hkv, int Nq, int Nk, int d_qk, int d_v, float scale, int causal,
                      void* workspace, size_t workspace_bytes, void* stream)
 {
     if (dtype != ATTN_BF16 && dtype != ATTN_F16) return ATTN_EUNSUPPORTED;
     if (!q || !k || !v || !o || !lse || !workspace) return ATTN_EINVAL;
-    if (int rc = check_strided(B, H, Hkv, N, d_qk, d_v)) return rc;
-    if (bad_stride(sq, B, N, H) || bad_stride(sk, B, N, Hkv) || bad_stride(sv, B, N, Hkv) || bad_stride(so, B, N, H))
+    if (int rc = check_strided(B, H, Hkv, Nq, Nk, d_qk, d_v)) return rc;
+    if (causal && Nk < Nq) return ATTN_EINVAL;             // some query would see no key
+    if (bad_stride(sq, B, Nq, H) || bad_stride(sk, B, Nk, Hkv) || bad_stride(sv, B, Nk, Hkv) || bad_stride(so, B, Nq, H))
         return ATTN_EINVAL;
     if (!(scale > 0.0f) || !(scale < 1e30f)) return ATTN_EINVAL;
     if (misaligned(q, 16) || misaligned(k, 16) || misaligned(v, 16) || misaligned(o, 16) ||
         misaligned(lse, 4) || misaligned(workspace, 256))
         return ATTN_EINVAL;
-    if (workspace_bytes < attn_strided_workspace_bytes(B, H, Hkv, N, d_qk, d_v, 0)) return ATTN_EINVAL;
+    if (workspace_bytes < attn_strided_workspace_bytes(B, H, Hkv, Nq, Nk, d_qk, d_v, 0)) return ATTN_EINVAL;
     char* ws = static_cast<char*>(workspace);
-    int* cu = reinterpret_cast<int*>(ws);
-    if (attn::launch_uniform_cu(cu, B, N, stream) != 0) return ATTN_ELAUNCH;
+    int* cu_q = reinterpret_cast<int*>(ws);
+    int* cu_k = reinterpret_cast<int*>(ws + cu_bytes(B));
+    if (attn::launch_uniform_cu(cu_q, B, Nq, stream) != 0 || attn::launch_uniform_cu(cu_k, B, Nk, stream) != 0)
+        return ATTN_ELAUNCH;
     attn::VarlenStrides st = {};
-    st.q = as_packed(sq, N);
-    st.k = as_packed(sk, N);
-    st.v = as_packed(sv, N);
-    st.o = as_packed(so, N);
-    st.lse_head = N;                       // lse [B, H, N]
-    st.lse_batch = (long long)(H - 1) * N;
-    return varlen_fwd_run(dtype, q, k, v, o, lse, cu, cu, B, B * N, B * N, H, Hkv, d_qk, d_v, scale, causal,
-                          ws + cu_bytes(B), st, stream);
+    st.q = as_packed(sq, Nq);
+    st.k = as_packed(sk, Nk);
+    st.v = as_packed(sv, Nk);
+    st.o = as_packed(so, Nq);
+    st.lse_head = Nq;                      // lse [B, H, Nq]
+    st.lse_batch = (long long)(H - 1) * Nq;
+    return varlen_fwd_run(dtype, q, k, v, o, lse, cu_q, cu_k, B, B * Nq, B * Nk, H, Hkv, d_qk, d_v, scale, causal,
+                          ws + 2 * cu_bytes(B), st, stream);
 }
 
 int attn_bwd_strided(int dtype, const void* q, const attn_strides_t* sq, const void* k, const attn_strides_t* sk,
@@ -394,37 +398,40 @@ int attn_bwd_strided(int dtype, const void* q, const attn_strides_t* sq, const v
                      const void* d_o, const attn_strides_t* sdo, const float* lse,
                      void* dq, const attn_strides_t* sdq, void* dk, const attn_strides_t* sdk,
                      void* dv, const attn_strides_t* sdv,
-                     int B, int H, int Hkv, int N, int d_qk, int d_v, float scale, int causal,
+                     int B, int H, int Hkv, int Nq, int Nk, int d_qk, int d_v, float scale, int causal,
                      void* workspace, size_t workspace_bytes, void* stream)
 {
     if (dtype != ATTN_BF16 && dtype != ATTN_F16) return ATTN_EUNSUPPORTED;
     if (!q || !k || !v || !o || !d_o || !lse || !dq || !dk || !dv || !workspace) return ATTN_EINVAL;
-    if (int rc = check_strided(B, H, Hkv, N, d_qk, d_v)) return rc;
-    if (bad_stride(sq, B, N, H) || bad_stride(sk, B, N, Hkv) || bad_stride(sv, B, N, Hkv) || bad_stride(so, B, N, H) ||
-        bad_stride(sdo, B, N, H) || bad_stride(sdq, B, N, H) || bad_stride(sdk, B, N, Hkv) || bad_stride(sdv, B, N, Hkv))
+    if (int rc = check_strided(B, H, Hkv, Nq, Nk, d_qk, d_v)) return rc;
+    if (causal && Nk < Nq) return ATTN_EINVAL;
+    if (bad_stride(sq, B, Nq, H) || bad_stride(sk, B, Nk, Hkv) || bad_stride(sv, B, Nk, Hkv) || bad_stride(so, B, Nq, H) ||
+        bad_stride(sdo, B, Nq, H) || bad_stride(sdq, B, Nq, H) || bad_stride(sdk, B, Nk, Hkv) || bad_stride(sdv, B, Nk, Hkv))
         return ATTN_EINVAL;
     if (!(scale > 0.0f) || !(scale < 1e30f)) return ATTN_EINVAL;
     const void* ptrs[] = {q, k, v, o, d_o, dq, dk, dv};
     for (const void* p : ptrs)
         if (misaligned(p, 16)) return ATTN_EINVAL;
     if (misaligned(lse, 4) || misaligned(workspace, 256)) return ATTN_EINVAL;
-    if (workspace_bytes < attn_strided_workspace_bytes(B, H, Hkv, N, d_qk, d_v, 1)) return ATTN_EINVAL;
+    if (workspace_bytes < attn_strided_workspace_bytes(B, H, Hkv, Nq, Nk, d_qk, d_v, 1)) return ATTN_EINVAL;
     char* ws = static_cast<char*>(workspace);
-    int* cu = reinterpret_cast<int*>(ws);
-    if (attn::launch_uniform_cu(cu, B, N, stream) != 0) return ATTN_ELAUNCH;
+    int* cu_q = reinterpret_cast<int*>(ws);
+    int* cu_k = reinterpret_cast<int*>(ws + cu_bytes(B));
+    if (attn::launch_uniform_cu(cu_q, B, Nq, stream) != 0 || attn::launch_uniform_cu(cu_k, B, Nk, stream) != 0)
+        return ATTN_ELAUNCH;
     attn::VarlenStrides st = {};
-    st.q = as_packed(sq, N);
-    st.k = as_packed(sk, N);
-    st.v = as_packed(sv, N);
-    st.o = as_packed(so, N);
-    st.d_o = as_packed(sdo, N);
-    st.dq = as_packed(sdq, N);
-    st.dk = as_packed(sdk, N);
-    st.dv = as_packed(sdv, N);
-    st.lse_head = N;
-    st.lse_batch = (long long)(H - 1) * N;
-    return varlen_bwd_run(dtype, q, k, v, o, d_o, lse, dq, dk, dv, cu, cu, B, B * N, B * N, H, Hkv, d_qk, d_v,
-                          scale, causal, ws + cu_bytes(B), st, N, stream);
+    st.q = as_packed(sq, Nq);
+    st.k = as_packed(sk, Nk);
+    st.v = as_packed(sv, Nk);
+    st.o = as_packed(so, Nq);
+    st.d_o = as_packed(sdo, Nq);
+    st.dq = as_packed(sdq, Nq);
+    st.dk = as_packed(sdk, Nk);
+    st.dv = as_packed(sdv, Nk);
+    st.lse_head = Nq;
+    st.lse_batch = (long long)(H - 1) * Nq;
+    return varlen_bwd_run(dtype, q, k, v, o, d_o, lse, dq, dk, dv, cu_q, cu_k, B, B * Nq, B * Nk, H, Hkv, d_qk, d_v,
+                          scale, causal, ws + 2 * cu_bytes(B), st, Nq, stream);
 }
 
 const char* attn_strerror(int code)

@@ -130,26 +130,34 @@ def test_varlen_workspace_and_validation(L):
 
 def test_strided_validation(L):
     import paper_2603_05451_amd as A
-    # the cu_seqlens array ((B + 1) ints -> 256) precedes the variable-length workspace
-    assert A.attn_strided_workspace_bytes(2, 4, 2, 384, 128, 128, False) == 256 + \
+    # the two generated cu_seqlens arrays ((B + 1) ints -> 256 bytes each) precede the variable-length workspace
+    assert A.attn_strided_workspace_bytes(2, 4, 2, 384, 384, 128, 128, False) == 512 + \
         A.attn_varlen_workspace_bytes(2, 768, 768, 4, 2, 128, 128, False)
-    assert A.attn_strided_workspace_bytes(2, 4, 2, 100, 64, 64, True) == 256 + \
-        A.attn_varlen_workspace_bytes(2, 200, 200, 4, 2, 64, 64, True)
-    assert A.attn_strided_workspace_bytes(2, 4, 2, 0, 64, 64, True) == 0
-    assert A.attn_strided_workspace_bytes(2, 4, 2, 100, 80, 80, True) == 0
+    assert A.attn_strided_workspace_bytes(2, 4, 2, 100, 300, 64, 64, True) == 512 + \
+        A.attn_varlen_workspace_bytes(2, 200, 600, 4, 2, 64, 64, True)
+    assert A.attn_strided_workspace_bytes(2, 4, 2, 0, 100, 64, 64, True) == 0
+    assert A.attn_strided_workspace_bytes(2, 4, 2, 100, 0, 64, 64, True) == 0
+    assert A.attn_strided_workspace_bytes(2, 4, 2, 100, 100, 80, 80, True) == 0
     p = ctypes.c_void_p(0x1000)
     ok = ctypes.byref(A.AttnStrides(100 * 4 * 64, 4 * 64, 64))
-    call = lambda sq, so, N=100: L.attn_fwd_strided(A.ATTN_BF16, p, sq, p, ok, p, ok, p, so, p, 2, 4, 4, N, 64, 64,
-                                                    0.125, 0, p, 1 << 20, None)
+    call = lambda sq, so, N=100, Nk=100, causal=0: L.attn_fwd_strided(
+        A.ATTN_BF16, p, sq, p, ok, p, ok, p, so, p, 2, 4, 4, N, Nk, 64, 64, 0.125, causal, p, 1 << 20, None)
     assert call(None, ok) == A.ATTN_EINVAL                                              # strides missing
     assert call(ctypes.byref(A.AttnStrides(100 * 4 * 64, 4 * 64 + 4, 64)), ok) == A.ATTN_EINVAL   # not 16-byte steps
     assert call(ok, ctypes.byref(A.AttnStrides(0, 4 * 64, 64))) == A.ATTN_EINVAL        # batches on top of each other
     assert call(ok, ctypes.byref(A.AttnStrides(-8, 4 * 64, 64))) == A.ATTN_EINVAL
     assert call(ok, ok, N=0) == A.ATTN_EINVAL
-    assert L.attn_fwd_strided(7, p, ok, p, ok, p, ok, p, ok, p, 2, 4, 4, 100, 64, 64, 0.125, 0, p, 1 << 20,
+    assert call(ok, ok, Nk=0) == A.ATTN_EINVAL
+    assert call(ok, ok, N=100, Nk=99, causal=1) == A.ATTN_EINVAL                        # a query without a visible key
+    assert L.attn_fwd_strided(7, p, ok, p, ok, p, ok, p, ok, p, 2, 4, 4, 100, 100, 64, 64, 0.125, 0, p, 1 << 20,
                               None) == A.ATTN_EUNSUPPORTED                              # unknown dtype
-    assert L.attn_fwd_strided(A.ATTN_BF16, p, ok, p, ok, p, ok, p, ok, p, 2, 4, 4, 100, 64, 64, 0.125, 0, p, 256,
+    assert L.attn_fwd_strided(A.ATTN_BF16, p, ok, p, ok, p, ok, p, ok, p, 2, 4, 4, 100, 100, 64, 64, 0.125, 0, p, 256,
                               None) == A.ATTN_EINVAL                                    # workspace too small
+    bwd = lambda Nk, causal: L.attn_bwd_strided(
+        A.ATTN_BF16, p, ok, p, ok, p, ok, p, ok, p, ok, p, p, ok, p, ok, p, ok, 2, 4, 4, 100, Nk, 64, 64,
+        0.125, causal, p, 1 << 8, None)
+    assert bwd(99, 1) == A.ATTN_EINVAL and bwd(0, 0) == A.ATTN_EINVAL
+    assert bwd(100, 0) == A.ATTN_EINVAL                                                 # workspace too small
 
 
 def test_varlen_workload_recipe_is_deterministic():

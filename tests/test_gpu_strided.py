@@ -84,3 +84,67 @@ def test_padded_rows_leave_the_padding_untouched():
     o, _ = A.attn_fwd_strided(q, k, v, w.scale, True, o=wide[..., :128])
     torch.cuda.synchronize()
     assert torch.equal(wide[..., :128], o_ref) and (wide[..., 128:] == 7.0).all()
+
+
+CROSS = [("d128_c_append", 128, 128, 4, 2, 200, 457, True, 90), ("d64_nc_more_queries", 64, 64, 2, 2, 300, 77, False, 91),
+         ("d128_c_decode", 128, 128, 4, 1, 1, 1000, True, 92), ("d192_c", 192, 128, 2, 1, 130, 384, True, 93),
+         ("d96_nc", 96, 96, 4, 2, 64, 640, False, 94), ("d256_c", 256, 256, 2, 1, 129, 258, True, 95)]
+
+
+@pytest.mark.parametrize("name,dqk,dv,H,Hkv,Nq,Nk,causal,seed", CROSS, ids=[c[0] for c in CROSS])
+def test_separate_query_and_key_counts(oracle, name, dqk, dv, H, Hkv, Nq, Nk, causal, seed):
+    """Equal-length batches with Nq queries against Nk keys per sequence (a chunk appended to a
+    cached prefix, one decoded token, cross-attention), q/k/v stored [B, heads, N, d].  Under the
+    causal mask the last query sees the last key, which the oracle expresses through the query
+    positions Nk - Nq ... Nk - 1."""
+    import paper_2603_05451_amd as A
+    B = 3
+    w = I.Workload("cross", B, H, Hkv, max(Nq, Nk), dqk, dv, causal, seed)
+    x = I.make_inputs(w)
+    cut = lambda n: x[n][:, :(Nq if n in ("q", "do") else Nk)]
+    bhsd = lambda t: t.permute(0, 2, 1, 3).contiguous().cuda().permute(0, 2, 1, 3)   # storage [B, heads, N, d]
+    q, k, v, do = (bhsd(cut(n)) for n in ("q", "k", "v", "do"))
+    assert not q.is_contiguous() or Nq == 1
+    o, lse = A.attn_fwd_strided(q, k, v, w.scale, causal)
+    dq, dk, dvv = A.attn_bwd_strided(q, k, v, o, do, lse, w.scale, causal)
+    torch.cuda.synchronize()
+    assert tuple(o.shape) == (B, Nq, H, dv) and tuple(lse.shape) == (B, H, Nq) and tuple(dk.shape) == (B, Nk, Hkv, dqk)
+    pos = np.arange(Nq) + (Nk - Nq)
+    f = lambda n: I.to_f64(cut(n))
+    ro, rlse = oracle.attn_fwd(f("q"), f("k"), f("v"), w.scale, causal, q_pos=pos)
+    rdq, rdk, rdv = oracle.attn_bwd(f("q"), f("k"), f("v"), f("do"), w.scale, causal, q_pos=pos)
+    got = [t.float().cpu().numpy() for t in (o, dq, dk, dvv)]
+    assert all(np.isfinite(t).all() for t in got)
+    assert np.abs(lse.cpu().numpy() - rlse).max() <= LSE_ABS
+    # few queries or keys: peaked softmaxes and outputs beyond magnitude 4; sums over the query
+    # heads of a group likewise -> the bound with the output-rounding term
+    few = min(Nq, Nk) < 32
+    close_q = assert_close_wide if few else assert_close
+    close_kv = assert_close_wide if few or H != Hkv else assert_close
+    close_q(got[0], ro, f"{name} O")
+    close_q(got[1], rdq, f"{name} dQ")
+    close_kv(got[2], rdk, f"{name} dK")
+    close_kv(got[3], rdv, f"{name} dV")
+
+
+def test_separate_counts_match_the_packed_calls_bitwise():
+    """The strided call with Nq != Nk is the variable-length call on the boundaries {0, Nq, ...} and
+    {0, Nk, ...}: same kernels, same tiles, same bits."""
+    import paper_2603_05451_amd as A
+    B, H, Hkv, Nq, Nk, d = 2, 4, 2, 200, 457, 128
+    w = I.Workload("cross", B, H, Hkv, Nk, d, d, True, 96)
+    x = I.make_inputs(w)
+    q, do = (x[n][:, :Nq].contiguous().cuda() for n in ("q", "do"))
+    k, v = x["k"].cuda(), x["v"].cuda()
+    o, lse = A.attn_fwd_strided(q, k, v, w.scale, True)
+    g = A.attn_bwd_strided(q, k, v, o, do, lse, w.scale, True)
+    cuq = torch.arange(0, B + 1, dtype=torch.int32, device="cuda") * Nq
+    cuk = torch.arange(0, B + 1, dtype=torch.int32, device="cuda") * Nk
+    flat = lambda t: t.reshape(-1, t.shape[2], t.shape[3])
+    o2, lse2 = A.attn_varlen_fwd(flat(q), flat(k), flat(v), cuq, w.scale, True, cu_seqlens_k=cuk)
+    g2 = A.attn_varlen_bwd(flat(q), flat(k), flat(v), o2, flat(do), lse2, cuq, w.scale, True, cu_seqlens_k=cuk)
+    torch.cuda.synchronize()
+    assert torch.equal(flat(o), o2)
+    assert torch.equal(lse.permute(1, 0, 2).reshape(H, B * Nq), lse2)
+    for a, b in zip(g, g2):
+        assert torch.equal(flat(a), b)
