@@ -10,21 +10,27 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libattn.so")
-SOURCES = ["attn_api.hip", "attn_fwd.hip", "attn_bwd.hip", "attn_varlen.hip", "exp2_probe.hip"]
+# VGPR_FORM: kernels that run one wave per SIMD may use the accumulation registers (AGPRs) next to
+# the 256 vector registers; by default the compiler then gives every MFMA an AGPR accumulator,
+# and where vector instructions read those accumulators every tile (softmax on the scores, dS from
+# dP) it shuttles hundreds of registers per tile between the two files.  With VGPR-form MFMAs the
+# AGPRs only hold spilled loop invariants.  Applied to the forward kernels (only head dim 256 runs
+# one wave per SIMD: +7 %, no other forward kernel changes) and to the kernels attn_bwd_all.inc
+# lists for the second pass over attn_bwd.hip.  The dK/dV kernels of d = 192 / 256 keep dK and dV,
+# which no vector instruction touches inside the loop, in AGPRs: they want the default.
+VGPR_FORM = ["-mllvm", "-amdgpu-mfma-vgpr-form=true"]
+# (source, object, additional flags)
+SOURCES = [("attn_api.hip", "attn_api.o", []),
+           ("attn_fwd.hip", "attn_fwd.o", VGPR_FORM),
+           ("attn_bwd.hip", "attn_bwd.o", []),
+           ("attn_bwd.hip", "attn_bwd_vgpr_form.o", ["-DATTN_BWD_VGPR_FORM_PART=1", *VGPR_FORM]),
+           ("attn_varlen.hip", "attn_varlen.o", []),
+           ("exp2_probe.hip", "exp2_probe.o", [])]
 # packed-fp32 instruction selection is switched off on purpose (device passes only; the
 # host pass prints a harmless "not a recognized feature" note).
 HIPCC_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
                "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
                "-Wno-unused-command-line-argument"]
-# Per-file additions.  Forward kernels that run one wave per SIMD (head dim 256) may use the
-# accumulation registers (AGPRs) next to the 256 vector registers; by default the compiler then
-# gives every MFMA an AGPR accumulator, and because the softmax reads the score accumulators
-# and the rescale touches the output ones it shuttles 260 registers per KV tile between the two
-# files.  With VGPR-form MFMAs the AGPRs only hold loop invariants: +7 % at d = 256, no other
-# forward kernel changes.  (The backward kernels of d = 192 / 256 keep dK and dV, which no
-# vector instruction touches inside the loop, in AGPRs: they want the default.)
-EXTRA_FLAGS = {"attn_fwd.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form=true"]}
-
 
 def _run(cmd, verbose):
     res = subprocess.run(cmd, capture_output=True, text=True)
@@ -42,9 +48,9 @@ def build_library(verbose: bool = False) -> str:
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
     tmp = tempfile.mkdtemp(prefix="libattn_build_")
     try:
-        objs = [os.path.join(tmp, s.replace(".hip", ".o")) for s in SOURCES]
-        jobs = [[hipcc, *HIPCC_FLAGS, *EXTRA_FLAGS.get(s, []), "-c", os.path.join(CSRC, s), "-o", o]
-                for s, o in zip(SOURCES, objs)]
+        objs = [os.path.join(tmp, obj) for _, obj, _ in SOURCES]
+        jobs = [[hipcc, *HIPCC_FLAGS, *extra, "-c", os.path.join(CSRC, src), "-o", os.path.join(tmp, obj)]
+                for src, obj, extra in SOURCES]
         with ThreadPoolExecutor(max_workers=min(len(jobs), os.cpu_count() or 1, 8)) as pool:
             list(pool.map(lambda c: _run(c, verbose), jobs))
         _run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB + ".tmp", *objs], verbose)

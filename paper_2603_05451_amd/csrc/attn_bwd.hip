@@ -34,6 +34,10 @@
 #include "common.h"
 #include "launch.h"
 
+#ifndef ATTN_BWD_VGPR_FORM_PART
+#define ATTN_BWD_VGPR_FORM_PART 0     // 1: the pass that compiles only the kernels listed in attn_bwd_all.inc
+#endif
+
 namespace attn {
 
 constexpr int BWD_BK = 128;   // dkdv: keys per block
@@ -68,6 +72,8 @@ namespace f16k {
 #include "attn_bwd_all.inc"
 }  // namespace f16k
 
+#if !ATTN_BWD_VGPR_FORM_PART
 int launch_bwd(const BwdArgs& a) { return a.f16 ? f16k::launch_bwd_dims(a) : launch_bwd_dims(a); }
+#endif
 
 }  // namespace attn
