@@ -23,7 +23,7 @@ PEAK_BF16_TFLOPS = 2500.0      # MI355X published dense bf16 MFMA peak
 # They cannot be measured from inside this process; None for any other workload.
 MEASURED_TRAFFIC = {
     "target_N8192_d128_nc": {"attn_fwd_wide_kernel": 201e6 + 68e6, "attn_bwd_dkdv_ws_kernel": 407e6 + 134e6,
-                             "attn_bwd_dq_wide_kernel": 271e6 + 67e6},
+                             "attn_bwd_dq_wide_kernel": 337e6 + 69e6},
 }
 PAPER_CONTEXT = "paper: up to 1613 TFLOP/s forward (71% of 2.25 PFLOP/s) on B200, BF16 -- other hardware, context only"
 
@@ -229,11 +229,15 @@ def main():
     f_dkdv = 2.0 * pairs * (2 * w.dqk + 2 * w.dv)     # S, dK contract/emit d_qk; dP, dV d_v
     f_dq = 2.0 * pairs * (2 * w.dqk + w.dv)           # S, dQ over d_qk; dP over d_v
     tf = lambda flops, ms: flops / ms / 1e9
-    dkdv_name = "attn_bwd_dkdv_ws_kernel" if w.dqk == 128 else "attn_bwd_dkdv_kernel"
+    dkdv_name = "attn_bwd_dkdv_ws_kernel" if w.dqk in (96, 128) else "attn_bwd_dkdv_kernel"
     # at d = 128 and N % 256 == 0 the library runs its 256-query blocks (forward always, dQ without a mask)
     wide = w.dqk == 128 and w.N % 256 == 0
     fwd_name = "attn_fwd_wide_kernel" if wide and w.N >= (8192 if w.causal else 2048) else "attn_fwd_kernel"
     dq_name = "attn_bwd_dq_wide_kernel" if wide and not w.causal and w.N >= 4096 else "attn_bwd_dq_kernel"
+    # the 256-query dQ kernel computes D and the base-2 LSE itself: the full backward then launches no
+    # prepare kernel (ATTN_BWD_PREPARE alone still does, which is what ms_prep timed above)
+    if dq_name == "attn_bwd_dq_wide_kernel":
+        ms_prep = 0.0
     out = {
         "metric": "attention fwd / bwd TFLOPs/s (bf16) and % of MI355X dense BF16 MFMA peak",
         "value": round(tf(f_fwd + f_bwd, ms_step), 2), "unit": "TFLOP/s",
