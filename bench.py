@@ -234,10 +234,9 @@ def main():
     wide = w.dqk == 128 and w.N % 256 == 0
     fwd_name = "attn_fwd_wide_kernel" if wide and w.N >= (8192 if w.causal else 2048) else "attn_fwd_kernel"
     dq_name = "attn_bwd_dq_wide_kernel" if wide and not w.causal and w.N >= 4096 else "attn_bwd_dq_kernel"
-    # the 256-query dQ kernel computes D and the base-2 LSE itself: the full backward then launches no
-    # prepare kernel (ATTN_BWD_PREPARE alone still does, which is what ms_prep timed above)
-    if dq_name == "attn_bwd_dq_wide_kernel":
-        ms_prep = 0.0
+    # the dQ kernel computes D and the base-2 LSE itself: the full backward launches no prepare kernel
+    # (ATTN_BWD_PREPARE alone still does, which is what ms_prep timed above)
+    ms_prep_alone, ms_prep = ms_prep, 0.0
     out = {
         "metric": "attention fwd / bwd TFLOPs/s (bf16) and % of MI355X dense BF16 MFMA peak",
         "value": round(tf(f_fwd + f_bwd, ms_step), 2), "unit": "TFLOP/s",
@@ -252,7 +251,8 @@ def main():
                 "frac_of_peak": round(tf(f_fwd, ms_fwd) / PEAK_BF16_TFLOPS, 4)},
         "bwd": {"ms": round(ms_bwd, 4), "tflops": round(tf(f_bwd, ms_bwd), 1),
                 "frac_of_peak": round(tf(f_bwd, ms_bwd) / PEAK_BF16_TFLOPS, 4),
-                "ms_prepare": round(ms_prep, 4), "ms_dkdv": round(ms_dkdv, 4), "ms_dq": round(ms_dq, 4)},
+                "ms_prepare": round(ms_prep, 4), "ms_dkdv": round(ms_dkdv, 4), "ms_dq": round(ms_dq, 4),
+                "ms_prepare_kernel_alone": round(ms_prep_alone, 4)},
         # dominant kernel = the dK/dV kernel (wave-specialised variant at d_qk = 128).  Its ALGORITHMIC
         # work is what it executes on the MFMA units: four contractions (S, dP, dV, dK) of
         # N^2 (d_qk or d_v) multiply-adds each.

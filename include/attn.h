@@ -83,15 +83,15 @@ int attn_bwd_ex(const void* q, const void* k, const void* v, const void* o, cons
                 int B, int H, int Hkv, int N, int d_qk, int d_v, float scale, int causal,
                 void* workspace, size_t workspace_bytes, void* stream);
 
-/* attn_bwd_ex restricted to a subset of its three kernels, for per-kernel timing and
- * profiling (the backward of paper Sec. 3.2 is one logical step; this splits it at the
- * kernel boundaries).  phases is a bit mask: ATTN_BWD_PREPARE (-D and base-2 LSE into the
- * workspace), ATTN_BWD_DKDV (writes dk, dv), ATTN_BWD_DQ (writes dq).  All arguments as
- * attn_bwd_ex.  ATTN_BWD_DKDV and ATTN_BWD_DQ read what ATTN_BWD_PREPARE left in the
- * workspace and are independent of each other.  Exception: on shapes where the dQ kernel computes
- * -D and the base-2 LSE itself (d = 128, no mask, N >= 4096 and a multiple of 256) a call that
- * includes ATTN_BWD_DQ launches no prepare kernel; the dQ kernel runs first and leaves the same
- * values in the workspace for ATTN_BWD_DKDV (of the same or of a later call). */
+/* attn_bwd_ex restricted to a subset of its passes, for per-kernel timing and profiling (the
+ * backward of paper Sec. 3.2 is one logical step; this splits it at the kernel boundaries).
+ * phases is a bit mask: ATTN_BWD_PREPARE (-D and base-2 LSE into the workspace), ATTN_BWD_DKDV
+ * (writes dk, dv; reads -D and the base-2 LSE from the workspace), ATTN_BWD_DQ (writes dq).  All
+ * arguments as attn_bwd_ex.  The dQ kernel computes -D and the base-2 LSE of its own rows
+ * itself (the same values bit for bit as the prepare kernel) and writes them to the workspace,
+ * so a call whose mask includes ATTN_BWD_DQ launches no prepare kernel: the dQ kernel runs first
+ * and ATTN_BWD_DKDV, of the same or of a later call, reads what it left.  attn_bwd_ex is
+ * therefore two kernels; ATTN_BWD_PREPARE has an effect only in a mask without ATTN_BWD_DQ. */
 enum { ATTN_BWD_PREPARE = 1, ATTN_BWD_DKDV = 2, ATTN_BWD_DQ = 4, ATTN_BWD_ALL = 7 };
 int attn_bwd_phases(const void* q, const void* k, const void* v, const void* o, const void* d_o,
                     const float* lse, void* dq, void* dk, void* dv,
