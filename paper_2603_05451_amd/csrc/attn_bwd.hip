@@ -10,9 +10,8 @@
 //   bwd_dkdv    : one workgroup per KV tile looping over query tiles, dK and dV accumulated
 //                 on chip for the whole loop (the loop structure of paper Sec. 3.2.2).
 //   bwd_dq      : one workgroup per query tile looping over KV tiles, dQ accumulated on chip.
-//                 In the fixed-length calls it does the prepare kernel's work for its own rows,
-//                 runs first and replaces that kernel (which remains for the variable-length
-//                 calls and for attn_bwd_phases without the dQ pass).
+//                 It does the prepare kernel's work for its own rows, runs first and replaces
+//                 that kernel (which remains for attn_bwd_phases without the dQ pass).
 //
 // Why dQ has a kernel of its own.  The paper adds a dQ tile to global memory with atomics
 // in every inner iteration (Sec. 3.2.2) and halves their number with CTA pairs (Sec. 3.2.3).
