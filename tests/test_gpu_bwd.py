@@ -69,6 +69,32 @@ def test_bwd_is_bit_reproducible():
         assert np.array_equal(u, v)
 
 
+@pytest.mark.parametrize("dqk,dv,N,causal,seed", [(128, 128, 4096, False, 32), (128, 128, 384, True, 33),
+                                                  (64, 64, 256, False, 34), (96, 96, 384, True, 35),
+                                                  (192, 128, 256, True, 36), (256, 256, 256, False, 37)])
+def test_bwd_phases_compose(dqk, dv, N, causal, seed):
+    """The backward pass split at its kernel boundaries gives the bits of the whole call, in both
+    orders the workspace allows: the prepare kernel, then dK/dV, then dQ (the standalone prepare
+    kernel and the dQ kernel's own prologue must write the same -D and base-2 LSE), and dQ first,
+    then dK/dV on what it left."""
+    import paper_2603_05451_amd as A
+    w = I.Workload("phases", 2, 4, 2, N, dqk, dv, causal, seed)
+    x = I.make_inputs(w)
+    q, k, v, do = (x[n].cuda() for n in ("q", "k", "v", "do"))
+    o, lse = A.attn_fwd(q, k, v, w.scale, causal)
+    ref = A.attn_bwd(q, k, v, o, do, lse, w.scale, causal)
+    nbytes = A.attn_bwd_workspace_bytes(w.B, w.H, w.Hkv, N, dqk, dv)
+    for order in ((A.ATTN_BWD_PREPARE, A.ATTN_BWD_DKDV, A.ATTN_BWD_DQ), (A.ATTN_BWD_DQ, A.ATTN_BWD_DKDV),
+                  (A.ATTN_BWD_PREPARE | A.ATTN_BWD_DKDV, A.ATTN_BWD_DQ)):
+        ws = torch.full((nbytes,), 0xFF, dtype=torch.uint8, device="cuda")      # NaN bit patterns
+        got = [torch.full_like(t, float("nan")) for t in (q, k, v)]
+        for ph in order:
+            A.attn_bwd(q, k, v, o, do, lse, w.scale, causal, got[0], got[1], got[2], ws, phases=ph)
+        torch.cuda.synchronize()
+        for a, b in zip(got, ref):
+            assert torch.equal(a, b), f"phases {order}"
+
+
 FULL = [I.TARGET, I.SWEEP_D64_NC[0], I.SWEEP_D64_NC[5], I.SWEEP_D128_C[0], I.SWEEP_D128_C[4], I.GQA,
         I.MLA_OUTLIER]
 
