@@ -102,6 +102,8 @@ def test_separate_query_and_key_counts(oracle, name, dqk, dv, H, Hkv, Nq, Nk, ca
     w = I.Workload("cross", B, H, Hkv, max(Nq, Nk), dqk, dv, causal, seed)
     x = I.make_inputs(w)
     cut = lambda n: x[n][:, :(Nq if n in ("q", "do") else Nk)]
+    if name == "d128_c_append":      # one case in fp16 storage (the oracle sees the same fp16 values)
+        x = {n: t.float().to(torch.float16) for n, t in x.items()}
     bhsd = lambda t: t.permute(0, 2, 1, 3).contiguous().cuda().permute(0, 2, 1, 3)   # storage [B, heads, N, d]
     q, k, v, do = (bhsd(cut(n)) for n in ("q", "k", "v", "do"))
     assert not q.is_contiguous() or Nq == 1
