@@ -221,6 +221,11 @@ int attn_bwd_strided(int dtype, const void* q, const attn_strides_t* sq, const v
 enum { ATTN_EXP2_RATE_BLOCKS = 2048 };
 int attn_exp2_emulated(const float* x, float* y, size_t n, int degree, void* stream);
 long long attn_exp2_rate(float* out, int degree, int iters, void* stream);
+/* The same kernel with the section's partial emulation: of the 8 evaluations per thread and
+ * iteration, emulated_of_8 (0, 1, 2, 4 or 8; the paper emulates 10-25 % of a row) go through the
+ * degree-3 polynomial and the rest through the hardware instruction.  Other values:
+ * ATTN_EUNSUPPORTED.  Arguments and return value as attn_exp2_rate. */
+long long attn_exp2_rate_partial(float* out, int emulated_of_8, int iters, void* stream);
 
 /* Matrix-core ceiling probe (measurement only, like the two above): enqueues a kernel of
  * ATTN_MFMA_RATE_BLOCKS x 512 threads (two waves per SIMD on 256 CUs) that issues nothing but

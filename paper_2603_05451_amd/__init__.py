@@ -74,6 +74,8 @@ def lib():
         L.attn_exp2_emulated.restype = i
         L.attn_exp2_rate.argtypes = [vp, i, i, vp]
         L.attn_exp2_rate.restype = ctypes.c_longlong
+        L.attn_exp2_rate_partial.argtypes = [vp, i, i, vp]
+        L.attn_exp2_rate_partial.restype = ctypes.c_longlong
         L.attn_lds_rate.argtypes = [vp, i, i, vp]
         L.attn_lds_rate.restype = ctypes.c_longlong
         L.attn_mfma_rate.argtypes = [vp, i, i, vp]
@@ -337,6 +339,18 @@ def attn_exp2_rate(degree, iters, out=None, stream=None):
     if out is None:
         out = torch.empty(ATTN_EXP2_RATE_BLOCKS * 256, dtype=torch.float32, device="cuda")
     n = lib().attn_exp2_rate(ctypes.c_void_p(out.data_ptr()), int(degree), int(iters), _stream(stream))
+    if n <= 0:
+        _check(int(n) or ATTN_EINVAL)
+    return int(n), out
+
+
+def attn_exp2_rate_partial(emulated_of_8, iters, out=None, stream=None):
+    """attn_exp2_rate with emulated_of_8 of every 8 evaluations on the degree-3 polynomial and the
+    rest on the hardware instruction; returns (number of evaluations, out tensor)."""
+    import torch
+    if out is None:
+        out = torch.empty(ATTN_EXP2_RATE_BLOCKS * 256, dtype=torch.float32, device="cuda")
+    n = lib().attn_exp2_rate_partial(ctypes.c_void_p(out.data_ptr()), int(emulated_of_8), int(iters), _stream(stream))
     if n <= 0:
         _check(int(n) or ATTN_EINVAL)
     return int(n), out

@@ -65,6 +65,28 @@ __global__ void __launch_bounds__(256) exp2_rate_kernel(float* __restrict__ out,
     out[(size_t)blockIdx.x * 256 + threadIdx.x] = t;
 }
 
+// Partial emulation (paper Sec. 3.1.3: a share of every row goes through the polynomial, the rest
+// through the hardware unit, so that both work at once): EMU of the 8 evaluation slots of a thread
+// use the degree-3 polynomial, the others v_exp_f32.
+template <int EMU>
+__global__ void __launch_bounds__(256) exp2_rate_partial_kernel(float* __restrict__ out, int iters)
+{
+    float v[8], s[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) { v[e] = 0.03f * e + 1e-4f * threadIdx.x; s[e] = 0.f; }
+    for (int it = 0; it < iters; ++it)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const float r = e < EMU ? exp2_emulated<3>(v[e]) : __builtin_amdgcn_exp2f(v[e]);
+            s[e] += r;
+            v[e] = r - 1.0f;
+        }
+    float t = 0.f;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) t += s[e];
+    out[(size_t)blockIdx.x * 256 + threadIdx.x] = t;
+}
+
 // Matrix-core ceiling: nothing but v_mfma_f32_32x32x16_bf16 on register operands, two waves per
 // SIMD, four accumulation chains per wave.  With random operands the chip's power management
 // lowers the shader clock; the rate this kernel sustains is what any bf16 MFMA kernel on such
@@ -205,6 +227,24 @@ long long attn_exp2_rate(float* out, int degree, int iters, void* stream)
         case 3: e = launch_kernel(exp2_rate_kernel<3>, grid, block, 0, stream, out, iters); break;
         case 4: e = launch_kernel(exp2_rate_kernel<4>, grid, block, 0, stream, out, iters); break;
         case 5: e = launch_kernel(exp2_rate_kernel<5>, grid, block, 0, stream, out, iters); break;
+        default: return ATTN_EUNSUPPORTED;
+    }
+    if (e != hipSuccess) return ATTN_ELAUNCH;
+    return (long long)ATTN_EXP2_RATE_BLOCKS * 256 * 8 * iters;
+}
+
+long long attn_exp2_rate_partial(float* out, int emulated_of_8, int iters, void* stream)
+{
+    using namespace attn;
+    if (!out || iters <= 0) return ATTN_EINVAL;
+    const dim3 grid(ATTN_EXP2_RATE_BLOCKS), block(256);
+    hipError_t e;
+    switch (emulated_of_8) {
+        case 0: e = launch_kernel(exp2_rate_partial_kernel<0>, grid, block, 0, stream, out, iters); break;
+        case 1: e = launch_kernel(exp2_rate_partial_kernel<1>, grid, block, 0, stream, out, iters); break;
+        case 2: e = launch_kernel(exp2_rate_partial_kernel<2>, grid, block, 0, stream, out, iters); break;
+        case 4: e = launch_kernel(exp2_rate_partial_kernel<4>, grid, block, 0, stream, out, iters); break;
+        case 8: e = launch_kernel(exp2_rate_partial_kernel<8>, grid, block, 0, stream, out, iters); break;
         default: return ATTN_EUNSUPPORTED;
     }
     if (e != hipSuccess) return ATTN_ELAUNCH;

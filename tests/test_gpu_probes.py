@@ -73,6 +73,28 @@ def test_emulation_is_slower_than_the_hardware_instruction(capsys):
     assert rates[3] < rates[0] and rates[4] < rates[0] and rates[5] < rates[0]
 
 
+def test_partial_emulation_lowers_the_exponential_rate():
+    """Paper Sec. 3.1.3 runs 10-25 % of a row's exponentials on the FMA pipes next to the hardware
+    unit.  Here both issue from one vector port: every share of emulation lowers the total rate."""
+    import paper_2603_05451_amd as A
+    rates = {}
+    for emu in (0, 1, 2, 4, 8):
+        A.attn_exp2_rate_partial(emu, 64)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        n, out = A.attn_exp2_rate_partial(emu, 2000)
+        e1.record()
+        e1.synchronize()
+        assert torch.isfinite(out).all()
+        rates[emu] = n / (e0.elapsed_time(e1) * 1e-3) / 1e12
+    path = os.path.join(os.path.dirname(os.path.dirname(__file__)), "gpurun_out", "exp2_partial_rates.txt")
+    os.makedirs(os.path.dirname(path), exist_ok=True)
+    with open(path, "w") as f:
+        f.write("emulated evaluations of 8 (degree 3) : T evaluations / s\n" +
+                "\n".join(f"{k} : {v:.3f}" for k, v in rates.items()) + "\n")
+    assert rates[1] < rates[0] and rates[2] < rates[1] and rates[8] < rates[4] < rates[2]
+
+
 def test_matrix_core_ceiling_on_random_operands():
     """Pure-MFMA rate with constant and with N(0,1) operands: the second is the ceiling every bf16
     MFMA kernel on such data is bounded by (the power limit lowers the clock)."""
