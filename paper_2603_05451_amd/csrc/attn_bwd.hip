@@ -3,7 +3,7 @@
 //   dV = P^T dO,  dP = dO V^T,  dS = P o (dP - D),  dQ = scale dS K,  dK = scale dS^T Q
 // (paper Sec. 2.1) with P recomputed from Q, K and the saved row log-sum-exp.
 //
-// Three kernels:
+// Kernels (a backward call launches bwd_dq, then bwd_dkdv):
 //   bwd_prepare : D_i = sum_c dO_ic O_ic (the identity sum_j P_ij dP_ij = dO_i . O_i that
 //                 follows from the softmax Jacobian of Sec. 2.1), stored as -D_i, and LSE in
 //                 base-2 units.  HBM bound.
