@@ -1,7 +1,7 @@
 #!/usr/bin/env python3
 """Benchmark of the fused attention hot path (forward + backward) on one MI355X.
 
-One "step" = attn_fwd followed by attn_bwd (all three backward kernels) on the target
+One "step" = attn_fwd followed by attn_bwd (both backward kernels: dQ, then dK/dV) on the target
 workload: B=2, H=16, N=8192, d=128, non-causal, bf16, synthetic N(0,1) inputs resident in
 HBM.  FLOPs follow the paper's convention (Sec. 5): forward 4 N^2 d per head and batch,
 backward 2.5 x forward.  Prints ONE JSON line.
