@@ -22,6 +22,7 @@ VGPR_FORM = ["-mllvm", "-amdgpu-mfma-vgpr-form=true"]
 # (source, object, additional flags)
 SOURCES = [("attn_api.hip", "attn_api.o", []),
            ("attn_fwd.hip", "attn_fwd.o", VGPR_FORM),
+           ("attn_fwd_q64.hip", "attn_fwd_q64.o", []),
            ("attn_bwd.hip", "attn_bwd.o", []),
            ("attn_bwd.hip", "attn_bwd_vgpr_form.o", ["-DATTN_BWD_VGPR_FORM_PART=1", *VGPR_FORM]),
            ("attn_varlen.hip", "attn_varlen.o", []),

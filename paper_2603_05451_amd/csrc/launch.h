@@ -2,6 +2,7 @@
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stddef.h>
+#include <stdlib.h>
 #include <tuple>
 
 namespace attn {
@@ -94,6 +95,8 @@ struct LdsOptIn {
 // 0 on success, -2 unsupported head dims, -3 launch failure.
 int launch_fwd(const FwdArgs& a);
 int launch_bwd(const BwdArgs& a);
+// The 64-queries-per-wave forward kernel (d_qk = d_v = 128, fixed length, N % 256 = 0).
+int launch_fwd_q64(const FwdArgs& a);
 // cu[b] = b * N for b = 0 .. B (device): the equal-length batch as a packed one.
 int launch_uniform_cu(int* cu, int B, int N, void* stream);
 // Fills the two plan tables of the variable-length entry points on the device: 0 or -3.
