@@ -22,7 +22,7 @@ PEAK_BF16_TFLOPS = 2500.0      # MI355X published dense bf16 MFMA peak
 # --pmc runs, scaled by the same counters' reading for a 1 GiB copy; profiles/bench_target_*.md).
 # They cannot be measured from inside this process; None for any other workload.
 MEASURED_TRAFFIC = {
-    "target_N8192_d128_nc": {"attn_fwd_wide_kernel": 201e6 + 68e6, "attn_bwd_dkdv_ws_kernel": 407e6 + 134e6,
+    "target_N8192_d128_nc": {"attn_fwd_q64_kernel": None, "attn_bwd_dkdv_ws_kernel": 407e6 + 134e6,
                              "attn_bwd_dq_wide_kernel": 337e6 + 69e6},
 }
 PAPER_CONTEXT = "paper: up to 1613 TFLOP/s forward (71% of 2.25 PFLOP/s) on B200, BF16 -- other hardware, context only"
@@ -41,7 +41,7 @@ def event_ms(fn, n):
     return e0.elapsed_time(e1) / n
 
 
-def cpu_baseline(w, x, seconds_target=8.0):
+def cpu_baseline(w, x, seconds_target=4.0):
     """The fp64 oracle as it stands, timed on this machine's host cores, on a bounded sample of the
     same workload: a contiguous block of query rows of (batch 0, head 0) against all N keys,
     forward + backward.  FLOPs by the same convention as the GPU figure."""
@@ -230,9 +230,10 @@ def main():
     f_dq = 2.0 * pairs * (2 * w.dqk + w.dv)           # S, dQ over d_qk; dP over d_v
     tf = lambda flops, ms: flops / ms / 1e9
     dkdv_name = "attn_bwd_dkdv_ws_kernel" if w.dqk in (96, 128) else "attn_bwd_dkdv_kernel"
-    # at d = 128 and N % 256 == 0 the library runs its 256-query blocks (forward always, dQ without a mask)
+    # at d = 128 and N % 256 == 0 the library runs 256-query blocks: the forward kernel with 64 queries
+    # per wave on long sequences, the 8-wave dQ kernel without a mask
     wide = w.dqk == 128 and w.N % 256 == 0
-    fwd_name = "attn_fwd_wide_kernel" if wide and w.N >= (8192 if w.causal else 2048) else "attn_fwd_kernel"
+    fwd_name = "attn_fwd_q64_kernel" if wide and w.dv == 128 and w.N >= (8192 if w.causal else 2048) else "attn_fwd_kernel"
     dq_name = "attn_bwd_dq_wide_kernel" if wide and not w.causal and w.N >= 4096 else "attn_bwd_dq_kernel"
     # the dQ kernel computes D and the base-2 LSE itself: the full backward launches no prepare kernel
     # (ATTN_BWD_PREPARE alone still does, which is what ms_prep timed above)

@@ -10,8 +10,8 @@
 //   wave w = 32 query rows; it keeps its Q rows in registers for the whole kernel;
 //   K/V tiles of BN = 64 keys stream through LDS, double buffered, copied straight
 //   from global memory into LDS (no VGPR staging) one tile ahead of the compute.
-//   At d = 128 and long sequences a second form of the same kernel text runs instead: 8 waves
-//   = 256 queries per block (attn_fwd_wide_kernel), each K/V tile copied once per 256 queries.
+//   At d = 128 and long fixed-length sequences the kernel of attn_fwd_q64.hip runs instead (64
+//   queries per wave, one wave per SIMD).
 //
 // MFMA orientation.  Scores are computed TRANSPOSED, S^T = K Q^T (keys on the MFMA row
 // axis, queries on the column axis).  In the 32x32 accumulator layout a lane then owns
@@ -30,9 +30,6 @@ constexpr int FWD_BM = 128;   // query rows per block
 constexpr int FWD_BN = 64;    // keys per tile
 constexpr int FWD_NT = 256;
 
-#ifndef ATTN_FWD_OCC192
-#define ATTN_FWD_OCC192 2
-#endif
 // ---- bf16 kernels
 #define ATTN_ELEM bf16
 #define ATTN_ELEM8 bf16x8
@@ -46,11 +43,6 @@ constexpr int FWD_NT = 256;
 #undef ATTN_VARLEN
 #define ATTN_VARLEN 1
 #include "attn_fwd_kernel.inc"
-#undef ATTN_VARLEN
-#define ATTN_VARLEN 0
-#define ATTN_FWD_WIDE 1
-#include "attn_fwd_kernel.inc"
-#undef ATTN_FWD_WIDE
 #undef ATTN_VARLEN
 #include "attn_fwd_launch.inc"
 
@@ -68,11 +60,6 @@ namespace f16k {
 #undef ATTN_VARLEN
 #define ATTN_VARLEN 1
 #include "attn_fwd_kernel.inc"
-#undef ATTN_VARLEN
-#define ATTN_VARLEN 0
-#define ATTN_FWD_WIDE 1
-#include "attn_fwd_kernel.inc"
-#undef ATTN_FWD_WIDE
 #undef ATTN_VARLEN
 #include "attn_fwd_launch.inc"
 }  // namespace f16k

@@ -37,12 +37,6 @@ typedef __attribute__((ext_vector_type(2))) _Float16 elem2;
 #include "attn_fwd_q64_launch.inc"
 }  // namespace f16k
 
-#if Q64X_STAMPS
-extern "C" int attn_q64_debug_read(long long* host, int n)
-{
-    return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(q64_dbg), n * sizeof(long long));
-}
-#endif
 int launch_fwd_q64(const FwdArgs& a) { return a.f16 ? f16k::launch_fwd_q64_t(a) : launch_fwd_q64_t(a); }
 
 }  // namespace attn

@@ -36,21 +36,6 @@ __device__ void plan_build(const int* __restrict__ cu_q, const int* __restrict__
     // a sequence contributes its own tiles; query tiles of a sequence without keys are not listed
     auto own_tiles = [&](int ql, int kl) { return own_is_q ? (kl > 0 ? tiles(ql) : 0) : tiles(kl); };
     auto key_of = [&](int ql, int kl) { return bucket_of(tiles(own_is_q ? kl : ql)); };
-#ifdef ATTN_PLAN_GIVEN_ORDER   // measurement only: the batch order as given, no sort
-    if (tid == 0) {
-        int run = 0;
-        for (int b = 0; b < B; ++b) {
-            const int qs = cu_q[b], ql = cu_q[b + 1] - qs, ks = cu_k[b], kl = cu_k[b + 1] - ks;
-            const int nt = own_tiles(ql, kl);
-            for (int t = 0; t < nt && run < max_tiles; ++t, ++run) {
-                plan[2 * run] = make_int4(qs, ql, ks, kl);
-                plan[2 * run + 1] = make_int4(nt - 1 - t, kPlanUsed, b, 0);
-            }
-        }
-    }
-    __syncthreads();
-    return;
-#endif
     for (int b = tid; b < B; b += PLAN_NT) {
         const int ql = cu_q[b + 1] - cu_q[b], kl = cu_k[b + 1] - cu_k[b];
         const int nt = own_tiles(ql, kl);

@@ -62,7 +62,7 @@ def test_fwd_full_size_sampled_rows(oracle, w):
     o, lse = gpu_fwd(w, x)
     assert np.isfinite(o).all() and np.isfinite(lse).all()
     rng = np.random.default_rng(w.seed)
-    rows = np.unique(np.concatenate([[0, 1, 31, 32, 63, 64, 127, 128, w.N - 129, w.N - 128, w.N - 1],
+    rows = np.unique(np.concatenate([[0, 1, 31, 32, 63, 64, 127, 128, 255, 256, w.N - 257, w.N - 256, w.N - 129, w.N - 128, w.N - 1],
                                      rng.integers(0, w.N, 48)]))
     G = w.H // w.Hkv
     for b, kvh in {(0, 0), (w.B - 1, w.Hkv - 1)}:
@@ -79,3 +79,44 @@ def test_fwd_full_size_sampled_rows(oracle, w):
             assert_close(o[b:b + 1, :, hs][:, rows], ro, f"O rows {w.name} b{b} kvh{kvh}")
         err = np.abs(lse[b:b + 1, hs][:, :, rows] - rlse).max()
         assert err <= LSE_ABS, f"LSE {w.name}: {err:.3e}"
+
+
+Q64 = [I.Workload("q64_nc_2048", 1, 3, 1, 2048, 128, 128, False, 31),
+       I.Workload("q64_nc_2304", 2, 2, 2, 2304, 128, 128, False, 32)]
+
+
+@pytest.mark.parametrize("w", Q64, ids=lambda w: w.name)
+def test_fwd_64_queries_per_wave_full_parity(oracle, w):
+    """Shapes that run the kernel with 64 queries per wave (d = 128, N % 256 = 0, N >= 2048 without
+    a mask), small enough for the oracle to compute every row: 8 and 9 query blocks of 256, GQA and
+    MHA, key loops of 32 and 36 tiles."""
+    x = I.make_inputs(w, with_do=False)
+    o, lse = gpu_fwd(w, x)
+    ro, rlse = oracle.attn_fwd(I.to_f64(x["q"]), I.to_f64(x["k"]), I.to_f64(x["v"]), w.scale, w.causal)
+    assert_close(o, ro, f"O {w.name}")
+    assert np.abs(lse - rlse).max() <= LSE_ABS, f"LSE {w.name}: {np.abs(lse - rlse).max():.3e}"
+
+
+@pytest.mark.parametrize("causal,N", [(False, 2048), (True, 8192)])
+def test_fwd_growing_scores_restart_with_exact_maxima(oracle, causal, N):
+    """Scores that grow along the key axis by hundreds of binary orders: relative to the first
+    tile's maximum the exponentials overflow, so the pipelined loop of the 64-queries-per-wave
+    kernel cannot produce these results; they come from its restart with a row maximum per tile
+    and the thresholded rescale (paper Sec. 3.1.4).  Compared on sampled rows."""
+    import paper_2603_05451_amd as A
+    g = torch.Generator("cpu").manual_seed(77)
+    H, d = 2, 128
+    q = torch.randn(1, N, H, d, generator=g).abs().to(torch.bfloat16)
+    k = (torch.randn(1, N, 1, d, generator=g).abs() * torch.linspace(0.2, 30.0, N).view(1, N, 1, 1)).to(torch.bfloat16)
+    v = torch.randn(1, N, 1, d, generator=g).to(torch.bfloat16)
+    scale = d ** -0.5
+    o, lse = A.attn_fwd(q.cuda(), k.cuda(), v.cuda(), scale, causal)
+    torch.cuda.synchronize()
+    o, lse = o.float().cpu().numpy(), lse.cpu().numpy()
+    assert np.isfinite(o).all() and np.isfinite(lse).all()
+    rng = np.random.default_rng(5)
+    rows = np.unique(np.concatenate([[0, 1, 63, 64, 255, 256, N - 257, N - 1], rng.integers(0, N, 40)]))
+    ro, rlse = oracle.attn_fwd(I.to_f64(q[:, rows]), I.to_f64(k), I.to_f64(v), scale, causal, q_pos=rows)
+    assert_close(o[:, rows], ro, f"O growing scores causal={causal}")
+    err = np.abs(lse[:, :, rows] - rlse).max()
+    assert err <= LSE_ABS, f"LSE growing scores: {err:.3e} (values up to {np.abs(rlse).max():.0f})"

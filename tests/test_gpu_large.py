@@ -43,15 +43,21 @@ def test_offsets_beyond_32_bits(oracle):
         assert_close_wide(f(dv, last), rdv[:, N - 128:], "large dV " + tag)
 
     # the same data as a packed batch of 33 equal sequences: the variable-length kernels, with their
-    # own offset arithmetic, must reproduce the bits (equal lengths, multiples of 128)
+    # own offset arithmetic.  Forward: the packed call runs 128-query blocks, attn_fwd at this length
+    # the kernel with 64 queries per wave (another summation order): one bf16 ulp.  Backward: the
+    # same kernels on the same tiles, from the same O and LSE: the same bits.
     del rdq, rdk, rdv, ro
     T = B * N
     cu = torch.arange(0, T + 1, N, dtype=torch.int32, device="cuda")
     p = lambda t: t.reshape(T, H, d)
     ov, lsev = A.attn_varlen_fwd(p(q), p(k), p(v), cu, scale, causal)
     torch.cuda.synchronize()
-    assert torch.equal(ov, p(o)) and torch.equal(lsev.reshape(H, B, N).permute(1, 0, 2), lse)
-    del o
-    gq, gk, gv = A.attn_varlen_bwd(p(q), p(k), p(v), ov, p(do), lsev, cu, scale, causal)
+    for lo in range(0, T, T // 33):
+        a, b_ = ov[lo:lo + T // 33].float(), p(o)[lo:lo + T // 33].float()
+        assert ((a - b_).abs() <= 2.0 ** -7 * b_.abs() + 1e-6).all()
+    assert (lsev.reshape(H, B, N).permute(1, 0, 2) - lse).abs().max().item() <= 2e-5
+    del ov, lsev
+    lse_packed = lse.permute(1, 0, 2).reshape(H, T).contiguous()
+    gq, gk, gv = A.attn_varlen_bwd(p(q), p(k), p(v), p(o), p(do), lse_packed, cu, scale, causal)
     torch.cuda.synchronize()
     assert torch.equal(gq, p(dq)) and torch.equal(gk, p(dk)) and torch.equal(gv, p(dv))
