@@ -46,7 +46,8 @@ enum {
     ATTN_EINVAL = -1,       /* null pointer, non-positive size, H % Hkv != 0, misaligned pointer,
                                workspace too small */
     ATTN_EUNSUPPORTED = -2, /* head dims or N outside the supported set */
-    ATTN_ELAUNCH = -3       /* the HIP runtime refused a launch */
+    ATTN_ELAUNCH = -3,      /* the HIP runtime refused a launch */
+    ATTN_ETOOLARGE = -4     /* attn_bwd_noalloc only: B * H * N above ATTN_NOALLOC_MAX_ROWS */
 };
 
 /* Forward pass (paper Sec. 2.1 first display; tiled evaluation per Sec. 3.1.4).
@@ -97,6 +98,24 @@ int attn_bwd_phases(const void* q, const void* k, const void* v, const void* o, 
                     const float* lse, void* dq, void* dk, void* dv,
                     int B, int H, int Hkv, int N, int d_qk, int d_v, float scale, int causal,
                     void* workspace, size_t workspace_bytes, void* stream, int phases);
+
+/* attn_bwd_ex for callers that cannot allocate device memory at all: code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc (and with it torch's allocator).  The
+ * workspace (-D and the base-2 LSE, 8 bytes per row of B * H * N) is an array inside the library's
+ * own device image, 8 MiB per GPU the library runs on, held until the process ends; this call and
+ * everything it reaches allocates and frees nothing.  Inputs, outputs, layouts and results are
+ * those of attn_bwd_ex (bit for bit).
+ *   - B * H * N must not exceed ATTN_NOALLOC_MAX_ROWS; beyond that the call returns
+ *     ATTN_ETOOLARGE with nothing enqueued.
+ *   - All calls on one GPU share that GPU's array: two calls that overlap in time on one GPU (on
+ *     different streams, or from different host threads) race on it.  Calls on one stream, or
+ *     ordered by events, are fine; nothing needs to be cleared between calls (every row that is
+ *     read has been written earlier in the same call). */
+#define ATTN_NOALLOC_MAX_ROWS (1 << 20)
+int attn_bwd_noalloc(const void* q, const void* k, const void* v, const void* o, const void* d_o,
+                     const float* lse, void* dq, void* dk, void* dv,
+                     int B, int H, int Hkv, int N, int d_qk, int d_v, float scale, int causal,
+                     void* stream);
 
 /* Bytes of workspace attn_bwd(_ex) needs for these sizes (0 if they are invalid):
  * D and the base-2 LSE, [B,H,N] fp32 each (256-byte aligned sections). */

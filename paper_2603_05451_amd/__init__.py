@@ -45,6 +45,8 @@ def lib():
         L.attn_bwd_ex.restype = i
         L.attn_bwd_phases.argtypes = [vp] * 9 + [i, i, i, i, i, i, f, i, vp, sz, vp, i]
         L.attn_bwd_phases.restype = i
+        L.attn_bwd_noalloc.argtypes = [vp] * 9 + [i, i, i, i, i, i, f, i, vp]
+        L.attn_bwd_noalloc.restype = i
         L.attn_bwd_workspace_bytes.argtypes = [i] * 6
         L.attn_bwd_workspace_bytes.restype = sz
         L.attn_fwd_dtype.argtypes = [i, vp, vp, vp, vp, vp, i, i, i, i, i, i, f, i, vp]
@@ -420,4 +422,23 @@ def attn_bwd(q, k, v, o, do, lse, scale, causal, dq=None, dk=None, dv=None, work
     else:
         raise ValueError("per-kernel phases are exposed for bf16 only")
     _check(rc)
+    return dq, dk, dv
+
+
+ATTN_NOALLOC_MAX_ROWS = 1 << 20
+
+
+def attn_bwd_noalloc(q, k, v, o, do, lse, scale, causal, dq, dk, dv, stream=None):
+    """attn_bwd with the library's built-in workspace (bf16; B * H * N <= ATTN_NOALLOC_MAX_ROWS).
+    The caller passes every output: nothing is allocated, here or in the library."""
+    B, N, H, dqk = q.shape
+    Hkv, dvd = k.shape[2], v.shape[3]
+    if _dtype_code(q) != ATTN_BF16:
+        raise ValueError("attn_bwd_noalloc takes bf16 tensors")
+    _check(lib().attn_bwd_noalloc(_dev_bf16(q, "q", like=q), _dev_bf16(k, "k", (B, N, Hkv, dqk), q),
+                                  _dev_bf16(v, "v", (B, N, Hkv, dvd), q), _dev_bf16(o, "o", (B, N, H, dvd), q),
+                                  _dev_bf16(do, "do", (B, N, H, dvd), q), ctypes.c_void_p(lse.data_ptr()),
+                                  _dev_bf16(dq, "dq", q.shape, q), _dev_bf16(dk, "dk", k.shape, q),
+                                  _dev_bf16(dv, "dv", v.shape, q), B, H, Hkv, N, dqk, dvd, float(scale),
+                                  int(bool(causal)), _stream(stream)))
     return dq, dk, dv

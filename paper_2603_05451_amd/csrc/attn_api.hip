@@ -146,6 +146,50 @@ int attn_bwd(const void* q, const void* k, const void* v, const void* o, const v
 }
 
 // ---------------------------------------------------------------------------------------------
+// backward pass without an allocation by anyone: the workspace lives in the library's device image
+
+namespace {
+
+// -D and the base-2 LSE of up to ATTN_NOALLOC_MAX_ROWS rows (B * H * N), laid out as
+// workspace_layout() lays out a caller's workspace of that many rows.  Every GPU the library runs
+// on holds its own copy, at its own address, until the process ends.
+constexpr size_t kScratchBytes = 2 * (size_t)ATTN_NOALLOC_MAX_ROWS * sizeof(float);
+static __device__ __align__(256) unsigned char scratch[kScratchBytes];
+
+// Device address of `scratch` on the current device (the array's name in host code is only a handle
+// for the runtime, not an address a kernel could use).  Looked up once per device; two host threads
+// racing here both store the same value.
+void* scratch_of_current_device(int* rc)
+{
+    static void* addr[64] = {};
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) { *rc = ATTN_ELAUNCH; return nullptr; }
+    if (!addr[dev]) {
+        void* p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) { *rc = ATTN_ELAUNCH; return nullptr; }
+        addr[dev] = p;
+    }
+    *rc = ATTN_OK;
+    return addr[dev];
+}
+
+}  // namespace
+
+int attn_bwd_noalloc(const void* q, const void* k, const void* v, const void* o, const void* d_o,
+                     const float* lse, void* dq, void* dk, void* dv,
+                     int B, int H, int Hkv, int N, int d_qk, int d_v, float scale, int causal,
+                     void* stream)
+{
+    if (int rc = check_sizes(B, H, Hkv, N, d_qk, d_v)) return rc;
+    if ((size_t)B * H * N > (size_t)ATTN_NOALLOC_MAX_ROWS) return ATTN_ETOOLARGE;
+    int rc = ATTN_OK;
+    void* ws = scratch_of_current_device(&rc);
+    if (!ws) return rc;
+    return bwd_impl(ATTN_BF16, q, k, v, o, d_o, lse, dq, dk, dv, B, H, Hkv, N, d_qk, d_v, scale, causal,
+                    ws, kScratchBytes, stream, ATTN_BWD_ALL);
+}
+
+// ---------------------------------------------------------------------------------------------
 // variable-length entry points
 
 namespace {
@@ -443,6 +487,8 @@ const char* attn_strerror(int code)
         case ATTN_EUNSUPPORTED: return "unsupported shape: (d_qk, d_v) must be (64,64), (96,96), (128,128), "
                                        "(192,128) or (256,256) and N a multiple of 128";
         case ATTN_ELAUNCH: return "HIP kernel launch failed";
+        case ATTN_ETOOLARGE: return "B * H * N exceeds ATTN_NOALLOC_MAX_ROWS, the size of the built-in workspace of "
+                                    "attn_bwd_noalloc: use attn_bwd_ex with a workspace of your own";
         default: return "unknown error code";
     }
 }
