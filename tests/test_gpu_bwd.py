@@ -7,7 +7,7 @@ import pytest
 import torch
 
 from paper_2603_05451_amd import inputs as I
-from parity import assert_close, assert_close_terms, term_magnitudes
+from parity import assert_close, assert_close_terms, rounded_reference, term_magnitudes
 
 pytestmark = pytest.mark.gpu
 
@@ -51,12 +51,13 @@ def test_bwd_small_full_parity(oracle, w):
     for b in range(w.B):
         for kvh in range(w.Hkv):
             hs = slice(kvh * G, (kvh + 1) * G)
-            _, a_dq, a_dk, a_dv = term_magnitudes(I.to_f64(x["q"][b, :, hs]), I.to_f64(x["k"][b, :, kvh]),
-                                                  I.to_f64(x["v"][b, :, kvh]), I.to_f64(x["do"][b, :, hs]),
-                                                  w.scale, w.causal)
-            assert_close_terms(dq[b, :, hs], rdq[b, :, hs], a_dq, f"dQ {w.name} b{b} kvh{kvh}")
-            assert_close_terms(dk[b, :, kvh], rdk[b, :, kvh], a_dk, f"dK {w.name} b{b} kvh{kvh}")
-            assert_close_terms(dv[b, :, kvh], rdv[b, :, kvh], a_dv, f"dV {w.name} b{b} kvh{kvh}")
+            args = (I.to_f64(x["q"][b, :, hs]), I.to_f64(x["k"][b, :, kvh]), I.to_f64(x["v"][b, :, kvh]),
+                    I.to_f64(x["do"][b, :, hs]), w.scale, w.causal)
+            _, a_dq, a_dk, a_dv = term_magnitudes(*args)
+            _, r_dq, r_dk, r_dv = rounded_reference(*args)
+            assert_close_terms(dq[b, :, hs], rdq[b, :, hs], a_dq, f"dQ {w.name} b{b} kvh{kvh}", r_dq)
+            assert_close_terms(dk[b, :, kvh], rdk[b, :, kvh], a_dk, f"dK {w.name} b{b} kvh{kvh}", r_dk)
+            assert_close_terms(dv[b, :, kvh], rdv[b, :, kvh], a_dv, f"dV {w.name} b{b} kvh{kvh}", r_dv)
 
 
 def test_bwd_is_bit_reproducible():
@@ -95,51 +96,72 @@ def test_bwd_phases_compose(dqk, dv, N, causal, seed):
             assert torch.equal(a, b), f"phases {order}"
 
 
-FULL = [I.TARGET, I.SWEEP_D64_NC[0], I.SWEEP_D64_NC[5], I.SWEEP_D128_C[0], I.SWEEP_D128_C[4], I.GQA,
-        I.MLA_OUTLIER]
+FULL = [I.TARGET, I.SWEEP_D64_NC[0], I.SWEEP_D64_NC[5], I.SWEEP_D128_C[0], I.SWEEP_D128_C[4], I.GQA]
 
 
 @pytest.mark.parametrize("w", FULL, ids=lambda w: w.name)
-def test_bwd_full_size_sampled(oracle, w):
-    """Benchmark sizes.  dQ rows are row-separable: sampled rows against the oracle.  dK/dV of a
-    key need every query row that sees it: for causal workloads the last 256 keys only receive
-    gradient from the last 256 rows, which the oracle computes exactly; for non-causal ones the
-    oracle runs one full (batch, KV head) group when N <= 8192, else the check is the linear
-    identity sum_j dV_j = sum_i dO_i (rows of P sum to one) plus dQ rows."""
+def test_bwd_full_size_one_complete_group(oracle, w):
+    """Benchmark sizes.  The oracle runs one complete (batch, KV head) group: all N query rows of all
+    G query heads of the group against all N keys, so dK and dV of EVERY key of the group are compared
+    element by element, from the first key tile (the longest query loop: G N / 64 rounds, head
+    switches included) to the last; dQ on sampled rows of the same group."""
     x = I.make_inputs(w)
     dq, dk, dv = gpu_fwd_bwd(w, x)
     for t in (dq, dk, dv):
         assert np.isfinite(t).all()
-    rng = np.random.default_rng(w.seed)
-    rows = np.unique(np.concatenate([[0, 1, 63, 64, 127, 128, w.N - 65, w.N - 64, w.N - 1],
-                                     rng.integers(0, w.N, 24)]))
     G = w.H // w.Hkv
     b, kvh = w.B - 1, w.Hkv - 1
     hs = slice(kvh * G, (kvh + 1) * G)
-    sl = lambda name, r: I.to_f64(x[name][b:b + 1, :, hs][:, r])
-    k = I.to_f64(x["k"][b:b + 1, :, kvh:kvh + 1])
-    v = I.to_f64(x["v"][b:b + 1, :, kvh:kvh + 1])
-    rdq, _, _ = oracle.attn_bwd(sl("q", rows), k, v, sl("do", rows), w.scale, w.causal, q_pos=rows)
-    if w.outlier_frac:
-        mags = lambda r: term_magnitudes(sl("q", r)[0], k[0, :, 0], v[0, :, 0], sl("do", r)[0], w.scale,
-                                         w.causal, q_pos=r)
-        cmp = lambda got, ref, mag, what: assert_close_terms(got, ref, mag, what)
-    else:
-        mags = lambda r: (None, None, None, None)
-        cmp = lambda got, ref, mag, what: assert_close(got, ref, what)
-    cmp(dq[b, :, hs][rows], rdq[0], mags(rows)[1], f"dQ rows {w.name}")
-    if w.causal:
-        tail = np.arange(w.N - 256, w.N)
-        _, rdk, rdv = oracle.attn_bwd(sl("q", tail), k, v, sl("do", tail), w.scale, True, q_pos=tail)
-        _, _, a_dk, a_dv = mags(tail)
-        cmp(dk[b, tail, kvh], rdk[0, tail, 0], None if a_dk is None else a_dk[tail], f"dK tail {w.name}")
-        cmp(dv[b, tail, kvh], rdv[0, tail, 0], None if a_dv is None else a_dv[tail], f"dV tail {w.name}")
-    elif w.N <= 8192:
-        allrows = np.arange(w.N)
-        _, rdk, rdv = oracle.attn_bwd(sl("q", allrows), k, v, sl("do", allrows), w.scale, False)
-        assert_close(dk[b:b + 1, :, kvh:kvh + 1], rdk, f"dK {w.name}")
-        assert_close(dv[b:b + 1, :, kvh:kvh + 1], rdv, f"dV {w.name}")
-    else:
-        want = I.to_f64(x["do"][b, :, hs]).sum(axis=(0, 1))
-        got = dv[b, :, kvh].astype(np.float64).sum(axis=0)
-        assert np.abs(got - want).max() <= 2e-2 * np.sqrt(w.N), "sum_j dV_j != sum_i dO_i"
+    f = lambda name, heads: I.to_f64(x[name][b:b + 1, :, heads])
+    rdq, rdk, rdv = oracle.attn_bwd(f("q", hs), f("k", slice(kvh, kvh + 1)), f("v", slice(kvh, kvh + 1)), f("do", hs),
+                                    w.scale, w.causal)
+    assert_close(dk[b:b + 1, :, kvh:kvh + 1], rdk, f"dK all keys {w.name}")
+    assert_close(dv[b:b + 1, :, kvh:kvh + 1], rdv, f"dV all keys {w.name}")
+    # the first key tile separately: its error must not hide in the norm of the whole group
+    assert_close(dk[b:b + 1, :128, kvh:kvh + 1], rdk[:, :128], f"dK keys 0-127 {w.name}")
+    assert_close(dv[b:b + 1, :128, kvh:kvh + 1], rdv[:, :128], f"dV keys 0-127 {w.name}")
+    rng = np.random.default_rng(w.seed)
+    rows = np.unique(np.concatenate([[0, 1, 63, 64, 127, 128, 255, 256, w.N - 65, w.N - 64, w.N - 1],
+                                     rng.integers(0, w.N, 24)]))
+    assert_close(dq[b:b + 1, rows][:, :, hs], rdq[:, rows], f"dQ rows {w.name}")
+
+
+def test_bwd_heavy_tailed_full_size(oracle):
+    """The (192, 128) workload at N = 32768 with 1 % of the q, k entries multiplied by 8: one head with
+    all 32768 query rows through the oracle (about a minute of CPU), dK and dV compared on the first
+    256 keys and on 256 keys drawn at random, dQ on sampled rows; under the term-scaled gate, audited
+    against the bf16-rounded definition (parity.py)."""
+    w = I.MLA_OUTLIER
+    x = I.make_inputs(w)
+    dq, dk, dv = gpu_fwd_bwd(w, x)
+    for t in (dq, dk, dv):
+        assert np.isfinite(t).all()
+    b, h = 0, w.H - 1
+    kvh = h // (w.H // w.Hkv)
+    f = lambda name, hh: I.to_f64(x[name][b:b + 1, :, hh:hh + 1])
+    q, k, v, do = f("q", h), f("k", kvh), f("v", kvh), f("do", h)
+    rdq, rdk, rdv = oracle.attn_bwd(q, k, v, do, w.scale, True)
+    rng = np.random.default_rng(55)
+    keys = np.unique(np.concatenate([np.arange(256), rng.integers(256, w.N, 256)]))
+    rows = np.unique(np.concatenate([[0, 1, 63, 64, 255, 256, w.N - 257, w.N - 1], rng.integers(0, w.N, 56)]))
+    # magnitudes of the summed terms and the bf16-rounded definition: dQ is separable by query row;
+    # dK / dV of a key collect every later query row, accumulated over blocks of rows
+    a_dk = np.zeros((w.N, w.dqk)); a_dv = np.zeros((w.N, w.dv))
+    r_dk = np.zeros((w.N, w.dqk)); r_dv = np.zeros((w.N, w.dv))
+    from parity import to_bf16
+    for lo in range(0, w.N, 2048):
+        r = np.arange(lo, lo + 2048)
+        args = (q[0, r], k[0, :, 0], v[0, :, 0], do[0, r], w.scale, True)
+        _, _, ak, av = term_magnitudes(*args, q_pos=r)
+        a_dk += ak; a_dv += av
+        _, _, rk, rv = rounded_reference(*args, q_pos=r, round_kv=False)
+        r_dk += rk; r_dv += rv
+    r_dk, r_dv = to_bf16(r_dk), to_bf16(r_dv)
+    assert_close_terms(dk[b, keys, kvh], rdk[0, keys, 0], a_dk[keys], "dK first 256 + random 256 keys, heavy tails", r_dk[keys])
+    assert_close_terms(dv[b, keys, kvh], rdv[0, keys, 0], a_dv[keys], "dV first 256 + random 256 keys, heavy tails", r_dv[keys])
+    args = (q[0, rows], k[0, :, 0], v[0, :, 0], do[0, rows], w.scale, True)
+    a_dq = term_magnitudes(*args, q_pos=rows)[1]
+    r_dq = rounded_reference(*args, q_pos=rows)[1]
+    assert_close_terms(dq[b, rows, h:h + 1], rdq[0, rows], a_dq, "dQ rows, heavy tails", r_dq)
+    # a fixed ceiling on the plain maximum error next to the scaled gate (observed 7.8e-2 for dQ)
+    assert np.abs(dq[b, rows, h:h + 1] - rdq[0, rows]).max() <= 0.10

@@ -4,7 +4,7 @@ import pytest
 import torch
 
 from paper_2603_05451_amd import inputs as I
-from parity import LSE_ABS, assert_close, assert_close_terms, term_magnitudes
+from parity import LSE_ABS, assert_close, assert_close_terms, rounded_reference, term_magnitudes
 
 pytestmark = pytest.mark.gpu
 
@@ -43,9 +43,10 @@ def test_fwd_small_full_parity(oracle, w):
         for b in range(w.B):
             for kvh in range(w.Hkv):
                 hs = slice(kvh * G, (kvh + 1) * G)
-                a_o = term_magnitudes(I.to_f64(x["q"][b, :, hs]), I.to_f64(x["k"][b, :, kvh]),
-                                      I.to_f64(x["v"][b, :, kvh]), np.zeros((w.N, G, w.dv)), w.scale, w.causal)[0]
-                assert_close_terms(o[b, :, hs], ro[b, :, hs], a_o, f"O {w.name} b{b} kvh{kvh}")
+                args = (I.to_f64(x["q"][b, :, hs]), I.to_f64(x["k"][b, :, kvh]), I.to_f64(x["v"][b, :, kvh]),
+                        np.zeros((w.N, G, w.dv)), w.scale, w.causal)
+                assert_close_terms(o[b, :, hs], ro[b, :, hs], term_magnitudes(*args)[0], f"O {w.name} b{b} kvh{kvh}",
+                                   rounded_reference(*args)[0])
     else:
         assert_close(o, ro, f"O {w.name}")
     assert np.abs(lse - rlse).max() <= LSE_ABS, f"LSE {w.name}: {np.abs(lse - rlse).max():.3e}"
@@ -72,9 +73,9 @@ def test_fwd_full_size_sampled_rows(oracle, w):
         v = I.to_f64(x["v"][b:b + 1, :, kvh:kvh + 1])
         ro, rlse = oracle.attn_fwd(q, k, v, w.scale, w.causal, q_pos=rows)
         if w.outlier_frac:
-            a_o = term_magnitudes(q[0], k[0, :, 0], v[0, :, 0], np.zeros((len(rows), G, w.dv)), w.scale,
-                                  w.causal, q_pos=rows)[0]
-            assert_close_terms(o[b, :, hs][rows], ro[0], a_o, f"O rows {w.name} b{b} kvh{kvh}")
+            args = (q[0], k[0, :, 0], v[0, :, 0], np.zeros((len(rows), G, w.dv)), w.scale, w.causal)
+            assert_close_terms(o[b, :, hs][rows], ro[0], term_magnitudes(*args, q_pos=rows)[0],
+                               f"O rows {w.name} b{b} kvh{kvh}", rounded_reference(*args, q_pos=rows)[0])
         else:
             assert_close(o[b:b + 1, :, hs][:, rows], ro, f"O rows {w.name} b{b} kvh{kvh}")
         err = np.abs(lse[b:b + 1, hs][:, :, rows] - rlse).max()

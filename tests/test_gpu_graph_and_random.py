@@ -8,7 +8,7 @@ import pytest
 import torch
 
 from paper_2603_05451_amd import inputs as I
-from parity import LSE_ABS, term_magnitudes
+from parity import LSE_ABS, assert_close, assert_close_terms, rounded_reference, term_magnitudes
 
 pytestmark = pytest.mark.gpu
 
@@ -78,11 +78,6 @@ def test_random_shapes_and_length_mixes(oracle):
     variable-length entry points against the oracle, element by element."""
     import paper_2603_05451_amd as A
     rng = np.random.default_rng(2024)
-    # Gate: the absolute bound of the N(0,1) tolerance plus the first-order rounding terms of
-    # parity.py (output rounding and the bf16 rounding of P, dS and O, scaled by the sizes of the
-    # summed terms): with a handful of keys or queries the gradients are sums of a few hundred
-    # large cancelling terms, which the plain 2e-2 does not cover.
-    excess = lambda got, ref, mag: float((np.abs(got - ref) - (2e-2 + 2.0 ** -8 * (np.abs(ref) + mag))).max())
     for case in range(int(os.environ.get("ATTN_RANDOM_CASES", "25"))):     # more cases on request
         dqk, dv = [(64, 64), (96, 96), (128, 128), (192, 128), (256, 256)][case % 5]
         Hkv = int(rng.integers(1, 3))
@@ -111,6 +106,9 @@ def test_random_shapes_and_length_mixes(oracle):
         torch.cuda.synchronize()
         o, lse, dq, dk, dvv = (z.float().cpu().numpy() for z in (o, lse, dq, dk, dvv))
         tag = f"case {case}: d{dqk}/{dv} H{H}/{Hkv} causal={causal} q={qlens} k={klens}"
+        # references of the whole packed tensors, filled sequence by sequence
+        ro_all, rdq_all = np.zeros(o.shape), np.zeros(dq.shape)
+        rdk_all, rdv_all = np.zeros(dk.shape), np.zeros(dvv.shape)
         for b, (nq, nk) in enumerate(zip(qlens, klens)):
             sq, sk = slice(int(cuq[b]), int(cuq[b + 1])), slice(int(cuk[b]), int(cuk[b + 1]))
             if nq == 0:
@@ -121,12 +119,31 @@ def test_random_shapes_and_length_mixes(oracle):
             ro, rlse = oracle.attn_fwd(fq, fk, fv, scale, causal, q_pos=pos)
             rdq, rdk, rdv = oracle.attn_bwd(fq, fk, fv, fdo, scale, causal, q_pos=pos)
             assert np.abs(lse[:, sq][None] - rlse).max() <= LSE_ABS, tag
-            G = H // Hkv
-            worst = -1.0
-            for g in range(Hkv):
-                hs = slice(g * G, (g + 1) * G)
-                a_o, a_dq, a_dk, a_dv = term_magnitudes(fq[0][:, hs], fk[0][:, g], fv[0][:, g], fdo[0][:, hs], scale,
-                                                        causal, q_pos=pos)
-                worst = max(worst, excess(o[sq][:, hs], ro[0][:, hs], a_o), excess(dq[sq][:, hs], rdq[0][:, hs], a_dq),
-                            excess(dk[sk][:, g], rdk[0][:, g], a_dk), excess(dvv[sk][:, g], rdv[0][:, g], a_dv))
-            assert worst <= 0, f"{tag}, sequence {b}: excess {worst:.3e}"
+            ro_all[sq], rdq_all[sq], rdk_all[sk], rdv_all[sk] = ro[0], rdq[0], rdk[0], rdv[0]
+            if nk == 1:     # a single key: dS = 0, so dQ and dK are exactly zero
+                assert np.abs(dq[sq]).max() <= 1e-5 and np.abs(dk[sk]).max() <= 1e-5, tag
+            if nk < 32:
+                # A handful of keys: softmax weights of order 1 and |dS| of order |dP|, the regime of
+                # the heavy-tailed workload (parity.py).  These sequences take its term-scaled gate,
+                # with its audit against the bf16-rounded definition but without a norm ratio of their
+                # own (a few rows), and leave the whole-tensor comparison below (their slices of the
+                # references are set to the GPU's values).
+                G = H // Hkv
+                for g in range(Hkv):
+                    hs = slice(g * G, (g + 1) * G)
+                    args = (fq[0][:, hs], fk[0][:, g], fv[0][:, g], fdo[0][:, hs], scale, causal)
+                    a_o, a_dq, a_dk, a_dv = term_magnitudes(*args, q_pos=pos)
+                    r_o, r_dq, r_dk, r_dv = rounded_reference(*args, q_pos=pos)
+                    what = f"{tag} seq {b} (few keys)"
+                    assert_close_terms(o[sq][:, hs], ro[0][:, hs], a_o, "O " + what, r_o, None)
+                    if nk > 1:
+                        assert_close_terms(dq[sq][:, hs], rdq[0][:, hs], a_dq, "dQ " + what, r_dq, None)
+                        assert_close_terms(dk[sk][:, g], rdk[0][:, g], a_dk, "dK " + what, r_dk, None)
+                    assert_close_terms(dvv[sk][:, g], rdv[0][:, g], a_dv, "dV " + what, r_dv, None)
+                ro_all[sq], rdq_all[sq], rdk_all[sk], rdv_all[sk] = o[sq], dq[sq], dk[sk], dvv[sk]
+        # the one rule of parity.py: max(2e-2, one bf16 ulp) for every element, relative Frobenius 1e-2
+        # over each output tensor of the call
+        assert_close(o, ro_all, f"O {tag}")
+        assert_close(dq, rdq_all, f"dQ {tag}")
+        assert_close(dk, rdk_all, f"dK {tag}")
+        assert_close(dvv, rdv_all, f"dV {tag}")

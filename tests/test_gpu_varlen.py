@@ -7,7 +7,7 @@ import pytest
 import torch
 
 from paper_2603_05451_amd import inputs as I
-from parity import LSE_ABS, assert_close, assert_close_wide
+from parity import LSE_ABS, assert_close
 
 pytestmark = pytest.mark.gpu
 
@@ -123,11 +123,8 @@ def test_varlen_bwd_parity(oracle, name, lengths, H, Hkv, dqk, dv, causal, seed)
             assert_close(dvv[s][None], rdv, f"varlen dV {name} seq{b} len{n}")
             continue
         assert_close(dq[s][None], rdq, f"varlen dQ {name} seq{b} len{n}")
-        # dK / dV summed over the query heads of a group exceed magnitude 4 on the first keys of a
-        # causal sequence, where half a bf16 ulp of the output is 1.6e-2 already
-        close_kv = assert_close_wide if H != Hkv else assert_close
-        close_kv(dk[s][None], rdk, f"varlen dK {name} seq{b} len{n}")
-        close_kv(dvv[s][None], rdv, f"varlen dV {name} seq{b} len{n}")
+        assert_close(dk[s][None], rdk, f"varlen dK {name} seq{b} len{n}")
+        assert_close(dvv[s][None], rdv, f"varlen dV {name} seq{b} len{n}")
 
 
 def test_varlen_bwd_matches_fixed_length_and_is_reproducible():
@@ -218,7 +215,7 @@ def test_varlen_many_short_sequences(oracle):
         rdq, rdk, rdv = oracle.attn_bwd(f("q"), f("k"), f("v"), f("do"), scale, True)
         # short sequences give peaked softmaxes and gradients of magnitude 4 .. 8, where one bf16
         # half-ulp of the OUTPUT is 1.6e-2 already: absolute bound plus the output-rounding term
-        # (parity.assert_close_wide's bound, without the Frobenius part: sequences this short have
+        # (parity.assert_close's bound, without the Frobenius part: sequences this short have
         # exactly-zero reference rows)
         ok = lambda got, ref: (np.abs(got - ref) <= 2e-2 + 2.0 ** -8 * np.abs(ref)).all()
         assert ok(o[s][None], ro) and ok(dq[s][None], rdq) and ok(dk[s][None], rdk) and ok(dv[s][None], rdv)
@@ -353,9 +350,8 @@ def test_varlen_separate_query_and_key_lengths(oracle, name, lens, H, Hkv, dqk, 
         assert_close(dq[sq][None], rdq, "dQ " + tag)
         # dK / dV summed over the query heads of a group exceed magnitude 4 on the first keys of a
         # causal sequence: the output-rounding term joins the absolute bound there
-        close_kv = assert_close_wide if H != Hkv else assert_close
-        close_kv(dk[sk][None], rdk, "dK " + tag)
-        close_kv(dvv[sk][None], rdv, "dV " + tag)
+        assert_close(dk[sk][None], rdk, "dK " + tag)
+        assert_close(dvv[sk][None], rdv, "dV " + tag)
 
 
 def test_varlen_decode_step_matches_last_row_of_prefill():
