@@ -27,8 +27,13 @@
  *   - causal != 0: key j is visible to query i iff j <= i.
  *   - Supported shapes: (d_qk, d_v) in {(64,64), (96,96), (128,128), (192,128), (256,256)}; N a positive
  *     multiple of 128 (the attn_varlen_* entry points take any lengths).
- *   - Return value: ATTN_OK, or a negative code.  On any error nothing has been
- *     enqueued and no output has been touched.
+ *   - Return value: ATTN_OK, or a negative code.  ATTN_EINVAL, ATTN_EUNSUPPORTED and
+ *     ATTN_ETOOLARGE are found before anything is enqueued: no output has been touched.
+ *     ATTN_ELAUNCH (the HIP runtime refused a launch or an attribute) can come from any of the
+ *     launches of a call that has several (the backward pass: dQ kernel, then dK/dV kernel; the
+ *     variable-length and strided calls: a small table kernel first): the launches before the
+ *     failed one stay enqueued and write their outputs (dq, the workspace); the outputs of the
+ *     failed and later launches are untouched.
  *   - Re-entrant; no global state.  Calls on different streams may run concurrently
  *     as long as their outputs and workspaces do not overlap.
  */
@@ -67,10 +72,11 @@ int attn_fwd_ex(const void* q, const void* k, const void* v, void* o, float* lse
  *   workspace: device scratch of at least attn_bwd_workspace_bytes(...) bytes,
  *        256-byte aligned; contents on entry are ignored, contents on exit are
  *        unspecified; may be reused by the next call on the same stream.
- * Three kernels are enqueued: D = rowsum(dO o O) with the base-2 LSE; the dK/dV kernel
- * (one workgroup per KV tile, dK and dV accumulated on chip over all query tiles and all
- * query heads of the group: the loop structure of paper Sec. 3.2.2); and the dQ kernel
- * (one workgroup per query tile, dQ accumulated on chip over all KV tiles).  The paper
+ * Two kernels are enqueued, in this order: the dQ kernel (one workgroup per query tile, dQ
+ * accumulated on chip over all KV tiles; it also forms D = rowsum(dO o O) and the base-2 LSE of
+ * its rows and leaves them in the workspace), then the dK/dV kernel (one workgroup per KV tile,
+ * dK and dV accumulated on chip over all query tiles and all query heads of the group: the loop
+ * structure of paper Sec. 3.2.2).  The paper
  * accumulates dQ with global atomics inside the dK/dV loop (Sec. 3.2.2-3.2.3); on MI355X
  * those atomics are memory-side and cost more than recomputing S and dP, so dQ has its
  * own pass.  No atomics are used: results are bit-reproducible from run to run (the
@@ -142,8 +148,12 @@ size_t attn_bwd_workspace_bytes(int B, int H, int Hkv, int N, int d_qk, int d_v)
  *   workspace: attn_varlen_workspace_bytes(..., backward) bytes, 256-byte aligned; the forward
  *   call needs the backward = 0 size, the backward call the backward = 1 size.  Contents on entry
  *   are ignored.  All other conventions (device pointers, stream, alignment, head dims, error
- *   codes, nothing enqueued on error) are those of attn_fwd_ex / attn_bwd_ex.  Behaviour is
- *   undefined if the cu_seqlens arrays violate the conditions above. */
+ *   codes) are those of attn_fwd_ex / attn_bwd_ex.  The table kernel checks every sequence's
+ *   boundaries on the device against total_q and total_k: a sequence whose rows do not lie inside
+ *   the tensors (decreasing boundaries, boundaries past the totals) is left out, i.e. none of its
+ *   rows is read or written, and the other sequences are served.  The remaining conditions (a key
+ *   for every sequence with queries; keys >= queries under a causal mask) are not checked: rows
+ *   that violate them hold unspecified values, nothing outside the tensors is touched. */
 size_t attn_varlen_workspace_bytes(int B, int total_q, int total_k, int H, int Hkv, int d_qk, int d_v, int backward);
 int attn_varlen_fwd(const void* q, const void* k, const void* v, void* o, float* lse,
                     const int* cu_seqlens_q, const int* cu_seqlens_k, int B, int total_q, int total_k,

@@ -244,7 +244,7 @@ int varlen_fwd_run(int dtype, const void* q, const void* k, const void* v, void*
                    float scale, int causal, char* ws, const attn::VarlenStrides& st, void* stream)
 {
     const VarlenLayout w = varlen_layout(B, Tq, Tk, H);
-    if (cu_q && attn::launch_varlen_plan(cu_q, cu_k, B, ws + w.plan_q_off, w.max_tiles_q, nullptr, 0, stream) != 0)
+    if (cu_q && attn::launch_varlen_plan(cu_q, cu_k, B, Tq, Tk, ws + w.plan_q_off, w.max_tiles_q, nullptr, 0, stream) != 0)
         return ATTN_ELAUNCH;
     attn::FwdArgs a{q, k, v, o, lse, B, H, Hkv, 0, d_qk, d_v, scale, causal != 0, stream};
     a.plan = ws + w.plan_q_off;
@@ -262,7 +262,7 @@ int varlen_bwd_run(int dtype, const void* q, const void* k, const void* v, const
                    float scale, int causal, char* ws, const attn::VarlenStrides& st, int rows_per_batch, void* stream)
 {
     const VarlenLayout w = varlen_layout(B, Tq, Tk, H);
-    if (cu_q && attn::launch_varlen_plan(cu_q, cu_k, B, ws + w.plan_q_off, w.max_tiles_q,
+    if (cu_q && attn::launch_varlen_plan(cu_q, cu_k, B, Tq, Tk, ws + w.plan_q_off, w.max_tiles_q,
                                          ws + w.plan_k_off, w.max_tiles_k, stream) != 0)
         return ATTN_ELAUNCH;
     attn::BwdArgs a{q, k, v, o, d_o, lse, dq, dk, dv, B, H, Hkv, 0, d_qk, d_v, scale, causal != 0,
@@ -298,7 +298,7 @@ int attn_varlen_plan(const int* cu_seqlens_q, const int* cu_seqlens_k, int B, in
     const VarlenLayout w = varlen_layout(B, total_q, total_k, H);
     if (workspace_bytes < w.total_bwd) return ATTN_EINVAL;
     char* ws = static_cast<char*>(workspace);
-    return attn::launch_varlen_plan(cu_seqlens_q, cu_seqlens_k, B, ws + w.plan_q_off, w.max_tiles_q,
+    return attn::launch_varlen_plan(cu_seqlens_q, cu_seqlens_k, B, total_q, total_k, ws + w.plan_q_off, w.max_tiles_q,
                                     ws + w.plan_k_off, w.max_tiles_k, stream) == 0 ? ATTN_OK : ATTN_ELAUNCH;
 }
 

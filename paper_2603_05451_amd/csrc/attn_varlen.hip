@@ -13,7 +13,9 @@
 // from the last tile to the first (under a causal mask the last query tile has the longest key
 // loop; the dK/dV kernels read the index backwards for the same reason).  Unused entries up to
 // the table size are zero.  The kernels size their grids by the table sizes, host-side upper
-// bounds, because the host never reads the lengths.
+// bounds, because the host never reads the lengths; for the same reason the boundaries are checked
+// here, on the device, against the row counts the caller stated: a sequence that does not lie
+// inside the tensors is left out of both tables.
 #include "common.h"
 #include "launch.h"
 
@@ -23,7 +25,7 @@ constexpr int PLAN_NT = 1024;
 constexpr int PLAN_BUCKETS = 4096;      // loop lengths 0 .. 4095 tiles; longer ones share the top bucket
 
 // One table.  own/other: the side whose tiles are listed and the side they loop over.
-__device__ void plan_build(const int* __restrict__ cu_q, const int* __restrict__ cu_k, int B, bool own_is_q,
+__device__ void plan_build(const int* __restrict__ cu_q, const int* __restrict__ cu_k, int B, int Tq, int Tk, bool own_is_q,
                            int4* __restrict__ plan, int max_tiles, int* hist, int* start, int* part)
 {
     static_assert(PLAN_BUCKETS == 4 * PLAN_NT, "four buckets per thread in the scan below");
@@ -36,9 +38,14 @@ __device__ void plan_build(const int* __restrict__ cu_q, const int* __restrict__
     // a sequence contributes its own tiles; query tiles of a sequence without keys are not listed
     auto own_tiles = [&](int ql, int kl) { return own_is_q ? (kl > 0 ? tiles(ql) : 0) : tiles(kl); };
     auto key_of = [&](int ql, int kl) { return bucket_of(tiles(own_is_q ? kl : ql)); };
+    // A sequence whose rows do not lie inside the tensors (boundaries that decrease, or that run past
+    // the totals the caller stated) gets no tiles at all: nothing of it is read or written.
+    auto inside = [&](int qs, int ql, int ks, int kl) {
+        return qs >= 0 && ql >= 0 && qs <= Tq - ql && ks >= 0 && kl >= 0 && ks <= Tk - kl;
+    };
     for (int b = tid; b < B; b += PLAN_NT) {
-        const int ql = cu_q[b + 1] - cu_q[b], kl = cu_k[b + 1] - cu_k[b];
-        const int nt = own_tiles(ql, kl);
+        const int qs = cu_q[b], ql = cu_q[b + 1] - qs, ks = cu_k[b], kl = cu_k[b + 1] - ks;
+        const int nt = inside(qs, ql, ks, kl) ? own_tiles(ql, kl) : 0;
         if (nt > 0) atomicAdd(&hist[key_of(ql, kl)], nt);
     }
     __syncthreads();
@@ -67,7 +74,7 @@ __device__ void plan_build(const int* __restrict__ cu_q, const int* __restrict__
     __syncthreads();
     for (int b = tid; b < B; b += PLAN_NT) {
         const int qs = cu_q[b], ql = cu_q[b + 1] - qs, ks = cu_k[b], kl = cu_k[b + 1] - ks;
-        const int nt = own_tiles(ql, kl);
+        const int nt = inside(qs, ql, ks, kl) ? own_tiles(ql, kl) : 0;
         if (nt <= 0) continue;
         const int key = key_of(ql, kl);
         const int first = start[key] + atomicAdd(&hist[key], nt);
@@ -81,14 +88,14 @@ __device__ void plan_build(const int* __restrict__ cu_q, const int* __restrict__
 }
 
 __global__ void __launch_bounds__(PLAN_NT)
-varlen_plan_kernel(const int* __restrict__ cu_q, const int* __restrict__ cu_k, int B,
+varlen_plan_kernel(const int* __restrict__ cu_q, const int* __restrict__ cu_k, int B, int Tq, int Tk,
                    int4* __restrict__ plan_q, int max_tiles_q, int4* __restrict__ plan_k, int max_tiles_k)
 {
     __shared__ int hist[PLAN_BUCKETS];       // tiles per bucket, then next free tile per bucket
     __shared__ int start[PLAN_BUCKETS];      // first table entry of each bucket
     __shared__ int part[PLAN_NT];
-    plan_build(cu_q, cu_k, B, true, plan_q, max_tiles_q, hist, start, part);
-    if (plan_k) plan_build(cu_q, cu_k, B, false, plan_k, max_tiles_k, hist, start, part);   // backward only
+    plan_build(cu_q, cu_k, B, Tq, Tk, true, plan_q, max_tiles_q, hist, start, part);
+    if (plan_k) plan_build(cu_q, cu_k, B, Tq, Tk, false, plan_k, max_tiles_k, hist, start, part);   // backward only
 }
 
 __global__ void uniform_cu_kernel(int* __restrict__ cu, int B, int N)
@@ -102,10 +109,10 @@ int launch_uniform_cu(int* cu, int B, int N, void* stream)
     return launch_kernel(uniform_cu_kernel, dim3((B + 256) / 256), dim3(256), 0, stream, cu, B, N) == hipSuccess ? 0 : -3;
 }
 
-int launch_varlen_plan(const int* cu_q, const int* cu_k, int B, void* plan_q, int max_tiles_q,
+int launch_varlen_plan(const int* cu_q, const int* cu_k, int B, int Tq, int Tk, void* plan_q, int max_tiles_q,
                        void* plan_k, int max_tiles_k, void* stream)
 {
-    return launch_kernel(varlen_plan_kernel, dim3(1), dim3(PLAN_NT), 0, stream, cu_q, cu_k, B,
+    return launch_kernel(varlen_plan_kernel, dim3(1), dim3(PLAN_NT), 0, stream, cu_q, cu_k, B, Tq, Tk,
                          (int4*)plan_q, max_tiles_q, (int4*)plan_k, max_tiles_k) == hipSuccess ? 0 : -3;
 }
 

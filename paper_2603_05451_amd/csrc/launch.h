@@ -100,7 +100,7 @@ int launch_fwd_q64(const FwdArgs& a);
 // cu[b] = b * N for b = 0 .. B (device): the equal-length batch as a packed one.
 int launch_uniform_cu(int* cu, int B, int N, void* stream);
 // Fills the two plan tables of the variable-length entry points on the device: 0 or -3.
-int launch_varlen_plan(const int* cu_q, const int* cu_k, int B, void* plan_q, int max_tiles_q,
+int launch_varlen_plan(const int* cu_q, const int* cu_k, int B, int Tq, int Tk, void* plan_q, int max_tiles_q,
                        void* plan_k, int max_tiles_k, void* stream);
 
 }  // namespace attn

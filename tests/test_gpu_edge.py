@@ -130,3 +130,29 @@ def test_sweep_midpoints_sampled(oracle, w):
         _, rdk, rdv = oracle.attn_bwd(f("q", allrows), kk, vv, f("do", allrows), w.scale, False)
         assert_close(dk[b, :, h].float().cpu().numpy(), rdk[0, :, 0], f"dK all keys {w.name}")
         assert_close(dv[b, :, h].float().cpu().numpy(), rdv[0, :, 0], f"dV all keys {w.name}")
+
+
+def test_literal_north_star_entry_points_on_live_tensors():
+    """attn_fwd and attn_bwd, the two signatures with a single head dim d, called directly through
+    ctypes on live tensors: the bits of the attn_fwd_ex / attn_bwd_phases route the binding takes."""
+    import ctypes
+    import paper_2603_05451_amd as A
+    w = I.Workload("literal", 2, 4, 2, 384, 128, 128, True, 71)
+    x = I.make_inputs(w)
+    q, k, v, do = (x[n].cuda() for n in ("q", "k", "v", "do"))
+    o_ref, lse_ref = A.attn_fwd(q, k, v, w.scale, True)
+    g_ref = A.attn_bwd(q, k, v, o_ref, do, lse_ref, w.scale, True)
+    L = A.lib()
+    p = lambda t: ctypes.c_void_p(t.data_ptr())
+    o = torch.full_like(o_ref, float("nan")); lse = torch.full_like(lse_ref, float("nan"))
+    stream = ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+    assert L.attn_fwd(p(q), p(k), p(v), p(o), p(lse), w.B, w.H, w.Hkv, w.N, 128, ctypes.c_float(w.scale), 1, stream) == 0
+    nbytes = L.attn_bwd_workspace_bytes(w.B, w.H, w.Hkv, w.N, 128, 128)
+    ws = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+    got = [torch.full_like(t, float("nan")) for t in (q, k, v)]
+    assert L.attn_bwd(p(q), p(k), p(v), p(o), p(do), p(lse), p(got[0]), p(got[1]), p(got[2]),
+                      w.B, w.H, w.Hkv, w.N, 128, ctypes.c_float(w.scale), 1, p(ws), nbytes, stream) == 0
+    torch.cuda.synchronize()
+    assert torch.equal(o, o_ref) and torch.equal(lse, lse_ref)
+    for a, b in zip(got, g_ref):
+        assert torch.equal(a, b)

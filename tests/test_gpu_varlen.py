@@ -411,3 +411,36 @@ def test_unplanned_workspace_is_not_acted_on():
         A.attn_varlen_bwd(q, k, v, o, do, lse, None, scale, True, dq=g[0], dk=g[1], dv=g[2], workspace=ws, B=B)
         torch.cuda.synchronize()
         assert (o == 7.0).all() and (lse == 7.0).all() and all((t == 7.0).all() for t in g)
+
+
+def test_sequences_outside_the_tensors_are_left_out():
+    """cu_seqlens_k (then cu_seqlens_q) whose last entry runs past the stated total: the table kernel
+    leaves that sequence out, so none of its rows is read or written, every kernel ends normally, and
+    the other sequences come out bit for bit as in the sound call."""
+    import paper_2603_05451_amd as A
+    H, Hkv, d = 4, 2, 128
+    lens = [200, 130, 300]
+    x, cu, scale = packed_inputs(lens, H, Hkv, d, d, 91, with_do=True)
+    T = int(cu[-1])
+    q, k, v, do = (x[n].cuda() for n in ("q", "k", "v", "do"))
+    good = torch.from_numpy(cu).cuda()
+    o_ref, lse_ref = A.attn_varlen_fwd(q, k, v, good, scale, True)
+    g_ref = A.attn_varlen_bwd(q, k, v, o_ref, do, lse_ref, good, scale, True)
+    bad = good.clone(); bad[3] = T + 64                     # last sequence: rows past the end of the tensors
+    for cq, ck in ((good, bad), (bad, good), (bad, bad)):
+        o = torch.full_like(o_ref, 7.0); lse = torch.full_like(lse_ref, 7.0)
+        A.attn_varlen_fwd(q, k, v, cq, scale, True, o=o, lse=lse, cu_seqlens_k=ck)
+        grads = [torch.full_like(t, 7.0) for t in (q, k, v)]
+        A.attn_varlen_bwd(q, k, v, o_ref, do, lse_ref, cq, scale, True, dq=grads[0], dk=grads[1], dv=grads[2],
+                          cu_seqlens_k=ck)
+        torch.cuda.synchronize()
+        for b in range(3):
+            s = slice(int(cu[b]), int(cu[b + 1]))
+            if b < 2:
+                assert torch.equal(o[s], o_ref[s]) and torch.equal(lse[:, s], lse_ref[:, s])
+                for a, r in zip(grads, g_ref):
+                    assert torch.equal(a[s], r[s])
+            else:
+                assert (o[s] == 7.0).all() and (lse[:, s] == 7.0).all()
+                for a in grads:
+                    assert (a[s] == 7.0).all()
