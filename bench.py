@@ -22,7 +22,7 @@ PEAK_BF16_TFLOPS = 2500.0      # MI355X published dense bf16 MFMA peak
 # --pmc runs, scaled by the same counters' reading for a 1 GiB copy; profiles/bench_target_*.md).
 # They cannot be measured from inside this process; None for any other workload.
 MEASURED_TRAFFIC = {
-    "target_N8192_d128_nc": {"attn_fwd_q64_kernel": None, "attn_bwd_dkdv_ws_kernel": 407e6 + 134e6,
+    "target_N8192_d128_nc": {"attn_fwd_q64_kernel": None, "attn_bwd_dkdv_u_kernel": None,
                              "attn_bwd_dq_wide_kernel": 337e6 + 69e6},
 }
 PAPER_CONTEXT = "paper: up to 1613 TFLOP/s forward (71% of 2.25 PFLOP/s) on B200, BF16 -- other hardware, context only"
@@ -229,7 +229,8 @@ def main():
     f_dkdv = 2.0 * pairs * (2 * w.dqk + 2 * w.dv)     # S, dK contract/emit d_qk; dP, dV d_v
     f_dq = 2.0 * pairs * (2 * w.dqk + w.dv)           # S, dQ over d_qk; dP over d_v
     tf = lambda flops, ms: flops / ms / 1e9
-    dkdv_name = "attn_bwd_dkdv_ws_kernel" if w.dqk in (96, 128) else "attn_bwd_dkdv_kernel"
+    dkdv_name = ("attn_bwd_dkdv_u_kernel" if w.dqk == 128 and not w.causal else
+                 "attn_bwd_dkdv_ws_kernel" if w.dqk in (96, 128) else "attn_bwd_dkdv_kernel")
     # at d = 128 and N % 256 == 0 the library runs 256-query blocks: the forward kernel with 64 queries
     # per wave on long sequences, the 8-wave dQ kernel without a mask
     wide = w.dqk == 128 and w.N % 256 == 0
@@ -254,7 +255,7 @@ def main():
                 "frac_of_peak": round(tf(f_bwd, ms_bwd) / PEAK_BF16_TFLOPS, 4),
                 "ms_prepare": round(ms_prep, 4), "ms_dkdv": round(ms_dkdv, 4), "ms_dq": round(ms_dq, 4),
                 "ms_prepare_kernel_alone": round(ms_prep_alone, 4)},
-        # dominant kernel = the dK/dV kernel (wave-specialised variant at d_qk = 128).  Its ALGORITHMIC
+        # dominant kernel = the dK/dV kernel.  Its ALGORITHMIC
         # work is what it executes on the MFMA units: four contractions (S, dP, dV, dK) of
         # N^2 (d_qk or d_v) multiply-adds each.
         "roofline": {"kernel": dkdv_name, "bound": "mfma",

