@@ -23,7 +23,7 @@ PEAK_BF16_TFLOPS = 2500.0      # MI355X published dense bf16 MFMA peak
 # They cannot be measured from inside this process; None for any other workload.
 MEASURED_TRAFFIC = {
     "target_N8192_d128_nc": {"attn_fwd_q64_kernel": None, "attn_bwd_dkdv_u_kernel": None,
-                             "attn_bwd_dq_wide_kernel": 337e6 + 69e6},
+                             "attn_bwd_dq_q64_kernel": None},
 }
 PAPER_CONTEXT = "paper: up to 1613 TFLOP/s forward (71% of 2.25 PFLOP/s) on B200, BF16 -- other hardware, context only"
 
@@ -235,7 +235,7 @@ def main():
     # per wave on long sequences, the 8-wave dQ kernel without a mask
     wide = w.dqk == 128 and w.N % 256 == 0
     fwd_name = "attn_fwd_q64_kernel" if wide and w.dv == 128 and w.N >= (8192 if w.causal else 2048) else "attn_fwd_kernel"
-    dq_name = "attn_bwd_dq_wide_kernel" if wide and not w.causal and w.N >= 4096 else "attn_bwd_dq_kernel"
+    dq_name = "attn_bwd_dq_q64_kernel" if wide and w.dv == 128 and not w.causal and w.N >= 1024 else "attn_bwd_dq_kernel"
     # the dQ kernel computes D and the base-2 LSE itself: the full backward launches no prepare kernel
     # (ATTN_BWD_PREPARE alone still does, which is what ms_prep timed above)
     ms_prep_alone, ms_prep = ms_prep, 0.0

@@ -26,6 +26,7 @@ SOURCES = [("attn_api.hip", "attn_api.o", []),
            ("attn_bwd.hip", "attn_bwd.o", []),
            ("attn_bwd.hip", "attn_bwd_vgpr_form.o", ["-DATTN_BWD_VGPR_FORM_PART=1", *VGPR_FORM]),
            ("attn_bwd_dkdv_u.hip", "attn_bwd_dkdv_u.o", []),
+           ("attn_bwd_dq_q64.hip", "attn_bwd_dq_q64.o", []),
            ("attn_varlen.hip", "attn_varlen.o", []),
            ("exp2_probe.hip", "exp2_probe.o", [])]
 # packed-fp32 instruction selection is switched off on purpose (device passes only; the

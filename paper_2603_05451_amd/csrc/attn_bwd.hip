@@ -77,19 +77,25 @@ namespace f16k {
 #if !ATTN_BWD_VGPR_FORM_PART
 int launch_bwd(const BwdArgs& a)
 {
-    // d = 128, fixed length, no mask: the dK/dV pass runs the kernel of attn_bwd_dkdv_u.hip (one wave per
-    // SIMD doing all four contractions of its keys: 1-5 % faster than the wave-specialised kernel at
-    // every N from 512 to 16384, bit-identical results).  The dQ kernel, and with it -D and the
-    // base-2 LSE, comes first as in every backward call.
-    const bool unified = (a.phases & 2) && !a.plan && !a.causal && a.d_qk == 128 && a.d_v == 128 && a.N % 128 == 0;
-    if (!unified) return a.f16 ? f16k::launch_bwd_dims(a) : launch_bwd_dims(a);
-    BwdArgs first = a;
-    first.phases = a.phases & ~2;
-    if (first.phases) {
-        const int rc = a.f16 ? f16k::launch_bwd_dims(first) : launch_bwd_dims(first);
-        if (rc != 0) return rc;
+    // d = 128, fixed length, no mask: both passes have a kernel with one wave per SIMD of their own
+    // (attn_bwd_dq_q64.hip, attn_bwd_dkdv_u.hip), bit-identical to the kernels of this file and faster.
+    // The dQ kernel, and with it -D and the base-2 LSE, comes first as in every backward call.
+    auto generic = [&](int phases) {
+        BwdArgs part = a;
+        part.phases = phases;
+        return a.f16 ? f16k::launch_bwd_dims(part) : launch_bwd_dims(part);
+    };
+    const bool plain128 = !a.plan && !a.causal && a.d_qk == 128 && a.d_v == 128;
+    const bool dq_q64 = (a.phases & 4) && plain128 && a.N % 256 == 0 && a.N >= 1024;   // shorter: the 4-wave kernel wins
+    const bool dkdv_u = (a.phases & 2) && plain128 && a.N % 128 == 0;
+    if (!dq_q64 && !dkdv_u) return generic(a.phases);
+    if (dq_q64) {
+        if (const int rc = launch_bwd_dq_q64(a)) return rc;
+    } else if (a.phases & 5) {
+        if (const int rc = generic(a.phases & 5)) return rc;
     }
-    return launch_bwd_dkdv_u(a);
+    if (dkdv_u) return launch_bwd_dkdv_u(a);
+    return (a.phases & 2) ? generic(2) : 0;
 }
 #endif
 

@@ -1,0 +1,40 @@
+// dQ kernel of the backward pass at head dim 128 with 64 queries per wave (gfx950): fixed-length
+// batches without a mask.  What is computed is described in attn_bwd.hip; how, at the top of
+// attn_bwd_dq_q64_kernel.inc.  A translation unit of its own, like attn_fwd_q64.hip, whose
+// techniques it shares.
+#include "common.h"
+#include "launch.h"
+
+namespace attn {
+
+#define ATTN_ELEM bf16
+#define ATTN_ELEM8 bf16x8
+#define ATTN_ELEM4 bf16x4
+#include "elem.inc"
+#undef ATTN_ELEM
+#undef ATTN_ELEM8
+#undef ATTN_ELEM4
+#define ATTN_MFMA "v_mfma_f32_32x32x16_bf16"
+typedef bf16x2 elem2;
+#include "attn_bwd_dq_q64_kernel.inc"
+#undef ATTN_MFMA
+#include "attn_bwd_dq_q64_launch.inc"
+
+namespace f16k {
+#define ATTN_ELEM f16
+#define ATTN_ELEM8 f16x8
+#define ATTN_ELEM4 f16x4
+#include "elem.inc"
+#undef ATTN_ELEM
+#undef ATTN_ELEM8
+#undef ATTN_ELEM4
+#define ATTN_MFMA "v_mfma_f32_32x32x16_f16"
+typedef __attribute__((ext_vector_type(2))) _Float16 elem2;
+#include "attn_bwd_dq_q64_kernel.inc"
+#undef ATTN_MFMA
+#include "attn_bwd_dq_q64_launch.inc"
+}  // namespace f16k
+
+int launch_bwd_dq_q64(const BwdArgs& a) { return a.f16 ? f16k::launch_bwd_dq_q64_t(a) : launch_bwd_dq_q64_t(a); }
+
+}  // namespace attn
