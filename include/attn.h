@@ -239,40 +239,12 @@ int attn_bwd_strided(int dtype, const void* q, const attn_strides_t* sq, const v
                      void* workspace, size_t workspace_bytes, void* stream);
 
 /* Software 2^x of paper Sec. 3.1.3 (range reduction + degree-n minimax polynomial, p0 = 1, Horner
- * with FMAs, exponent splice), provided to measure it on this hardware; attn_fwd does not use
- * it (v_exp_f32 and the FMAs share one issue port on CDNA4, so emulation cannot add throughput).
+ * with FMAs, exponent splice), provided to measure its accuracy on this hardware; attn_fwd does not
+ * use it (v_exp_f32 and the FMAs share one issue port on CDNA4, so emulation cannot add throughput:
+ * the rate probes that show this live in a library of their own, include/attn_probes.h).
  *   attn_exp2_emulated: y[i] = 2^x[i] for n fp32 values; degree 3, 4 or 5, or 0 for the hardware
- *       instruction.  x, y: device pointers, 4-byte aligned, may not overlap partially.
- *   attn_exp2_rate: enqueues a pure-ALU kernel of ATTN_EXP2_RATE_BLOCKS x 256 threads, each
- *       doing 8 x iters evaluations, writing one float per thread to out (device,
- *       ATTN_EXP2_RATE_BLOCKS * 256 floats); returns the number of evaluations enqueued (> 0),
- *       or a negative error code.  The caller times it on the stream. */
-enum { ATTN_EXP2_RATE_BLOCKS = 2048 };
+ *       instruction.  x, y: device pointers, 4-byte aligned, may not overlap partially. */
 int attn_exp2_emulated(const float* x, float* y, size_t n, int degree, void* stream);
-long long attn_exp2_rate(float* out, int degree, int iters, void* stream);
-/* The same kernel with the section's partial emulation: of the 8 evaluations per thread and
- * iteration, emulated_of_8 (0, 1, 2, 4 or 8; the paper emulates 10-25 % of a row) go through the
- * degree-3 polynomial and the rest through the hardware instruction.  Other values:
- * ATTN_EUNSUPPORTED.  Arguments and return value as attn_exp2_rate. */
-long long attn_exp2_rate_partial(float* out, int emulated_of_8, int iters, void* stream);
-
-/* Matrix-core ceiling probe (measurement only, like the two above): enqueues a kernel of
- * ATTN_MFMA_RATE_BLOCKS x 512 threads (two waves per SIMD on 256 CUs) that issues nothing but
- * v_mfma_f32_32x32x16_bf16 on register operands, 32 x iters per wave, with constant operands
- * (random_operands = 0) or N(0,1)-like ones (!= 0: the data the attention workloads of paper
- * Sec. 5 use).  out: device, ATTN_MFMA_RATE_BLOCKS * 512 floats.  Returns the number of FLOPs
- * enqueued (> 0) or a negative error code; the caller times it on the stream. */
-enum { ATTN_MFMA_RATE_BLOCKS = 256 };
-long long attn_mfma_rate(float* out, int random_operands, int iters, void* stream);
-
-/* LDS read rate in the kernels' two access patterns, to put their LDS traffic in proportion:
- * enqueues ATTN_LDS_RATE_BLOCKS blocks of 256 threads (2 resident per CU) that read a swizzled
- * 64 x 128 tile of 16-bit elements over and over, pattern 0 with ds_read_b128 as the MFMA
- * A-operand fragments are read, pattern 1 with ds_read_b64_tr_b16 as the transposed fragments
- * are; writes one float per thread to out (device, ATTN_LDS_RATE_BLOCKS * 256 floats) and
- * returns the number of bytes read from LDS (> 0), or a negative error code. */
-#define ATTN_LDS_RATE_BLOCKS 512
-long long attn_lds_rate(float* out, int pattern, int iters, void* stream);
 
 /* Human-readable text for a return code (static storage). */
 const char* attn_strerror(int code);

@@ -74,14 +74,6 @@ def lib():
         L.attn_varlen_bwd.restype = i
         L.attn_exp2_emulated.argtypes = [vp, vp, sz, i, vp]
         L.attn_exp2_emulated.restype = i
-        L.attn_exp2_rate.argtypes = [vp, i, i, vp]
-        L.attn_exp2_rate.restype = ctypes.c_longlong
-        L.attn_exp2_rate_partial.argtypes = [vp, i, i, vp]
-        L.attn_exp2_rate_partial.restype = ctypes.c_longlong
-        L.attn_lds_rate.argtypes = [vp, i, i, vp]
-        L.attn_lds_rate.restype = ctypes.c_longlong
-        L.attn_mfma_rate.argtypes = [vp, i, i, vp]
-        L.attn_mfma_rate.restype = ctypes.c_longlong
         L.attn_strerror.argtypes = [i]
         L.attn_strerror.restype = ctypes.c_char_p
         L.attn_version.restype = i
@@ -321,9 +313,6 @@ def attn_bwd_strided(q, k, v, o, d_o, lse, scale, causal, dq=None, dk=None, dv=N
     return dq, dk, dv
 
 
-ATTN_EXP2_RATE_BLOCKS = 2048
-
-
 def attn_exp2_emulated(x, degree, y=None, stream=None):
     """y = 2^x elementwise on the GPU: polynomial emulation of degree 3/4/5, or 0 = v_exp_f32."""
     import torch
@@ -333,59 +322,6 @@ def attn_exp2_emulated(x, degree, y=None, stream=None):
     _check(lib().attn_exp2_emulated(ctypes.c_void_p(x.data_ptr()), ctypes.c_void_p(y.data_ptr()),
                                     x.numel(), int(degree), _stream(stream)))
     return y
-
-
-def attn_exp2_rate(degree, iters, out=None, stream=None):
-    """Enqueue the pure-ALU exp2 throughput kernel; returns (number of evaluations, out tensor)."""
-    import torch
-    if out is None:
-        out = torch.empty(ATTN_EXP2_RATE_BLOCKS * 256, dtype=torch.float32, device="cuda")
-    n = lib().attn_exp2_rate(ctypes.c_void_p(out.data_ptr()), int(degree), int(iters), _stream(stream))
-    if n <= 0:
-        _check(int(n) or ATTN_EINVAL)
-    return int(n), out
-
-
-def attn_exp2_rate_partial(emulated_of_8, iters, out=None, stream=None):
-    """attn_exp2_rate with emulated_of_8 of every 8 evaluations on the degree-3 polynomial and the
-    rest on the hardware instruction; returns (number of evaluations, out tensor)."""
-    import torch
-    if out is None:
-        out = torch.empty(ATTN_EXP2_RATE_BLOCKS * 256, dtype=torch.float32, device="cuda")
-    n = lib().attn_exp2_rate_partial(ctypes.c_void_p(out.data_ptr()), int(emulated_of_8), int(iters), _stream(stream))
-    if n <= 0:
-        _check(int(n) or ATTN_EINVAL)
-    return int(n), out
-
-
-ATTN_MFMA_RATE_BLOCKS = 256
-
-
-def attn_mfma_rate(random_operands, iters, out=None, stream=None):
-    """Enqueue the pure-MFMA ceiling kernel; returns (FLOPs enqueued, out tensor)."""
-    import torch
-    if out is None:
-        out = torch.empty(ATTN_MFMA_RATE_BLOCKS * 512, dtype=torch.float32, device="cuda")
-    n = lib().attn_mfma_rate(ctypes.c_void_p(out.data_ptr()), int(bool(random_operands)), int(iters),
-                             _stream(stream))
-    if n <= 0:
-        _check(int(n) or ATTN_EINVAL)
-    return int(n), out
-
-
-ATTN_LDS_RATE_BLOCKS = 512
-
-
-def attn_lds_rate(pattern, iters, out=None, stream=None):
-    """Enqueue the LDS read-rate kernel (pattern 0: ds_read_b128 A-operand fragments, 1: transposing
-    reads); returns (bytes read from LDS, out tensor)."""
-    import torch
-    if out is None:
-        out = torch.empty(ATTN_LDS_RATE_BLOCKS * 256, dtype=torch.float32, device="cuda")
-    n = lib().attn_lds_rate(ctypes.c_void_p(out.data_ptr()), int(pattern), int(iters), _stream(stream))
-    if n <= 0:
-        _check(int(n) or ATTN_EINVAL)
-    return int(n), out
 
 
 ATTN_BWD_PREPARE, ATTN_BWD_DKDV, ATTN_BWD_DQ, ATTN_BWD_ALL = 1, 2, 4, 7

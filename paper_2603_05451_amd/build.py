@@ -1,4 +1,5 @@
-"""Compile the HIP sources into libattn.so next to this file (hipcc, gfx950 only)."""
+"""Compile the HIP sources into libattn.so (the attention library) and libattn_probes.so (measurement
+probes, a library of their own) next to this file (hipcc, gfx950 only)."""
 from __future__ import annotations
 
 import os
@@ -10,6 +11,7 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libattn.so")
+PROBES_LIB = os.path.join(HERE, "libattn_probes.so")
 # VGPR_FORM: kernels that run one wave per SIMD may use the accumulation registers (AGPRs) next to
 # the 256 vector registers; by default the compiler then gives every MFMA an AGPR accumulator,
 # and where vector instructions read those accumulators every tile (softmax on the scores, dS from
@@ -28,7 +30,8 @@ SOURCES = [("attn_api.hip", "attn_api.o", []),
            ("attn_bwd_dkdv_u.hip", "attn_bwd_dkdv_u.o", []),
            ("attn_bwd_dq_q64.hip", "attn_bwd_dq_q64.o", []),
            ("attn_varlen.hip", "attn_varlen.o", []),
-           ("exp2_probe.hip", "exp2_probe.o", [])]
+           ("exp2_emulated.hip", "exp2_emulated.o", [])]
+PROBE_SOURCES = [("probes.hip", "probes.o", [])]
 # packed-fp32 instruction selection is switched off on purpose (device passes only; the
 # host pass prints a harmless "not a recognized feature" note).
 HIPCC_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
@@ -46,18 +49,20 @@ def _run(cmd, verbose):
 
 
 def build_library(verbose: bool = False) -> str:
-    """One hipcc process per source file (the two attention files dominate: every kernel body is
-    instantiated per head dim, mask, mode and element type), then one link step."""
+    """One hipcc process per source file (the attention files dominate: every kernel body is
+    instantiated per head dim, mask, mode and element type), then one link step per library."""
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
     tmp = tempfile.mkdtemp(prefix="libattn_build_")
     try:
-        objs = [os.path.join(tmp, obj) for _, obj, _ in SOURCES]
+        every = SOURCES + PROBE_SOURCES
         jobs = [[hipcc, *HIPCC_FLAGS, *extra, "-c", os.path.join(CSRC, src), "-o", os.path.join(tmp, obj)]
-                for src, obj, extra in SOURCES]
+                for src, obj, extra in every]
         with ThreadPoolExecutor(max_workers=min(len(jobs), os.cpu_count() or 1, 8)) as pool:
             list(pool.map(lambda c: _run(c, verbose), jobs))
-        _run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB + ".tmp", *objs], verbose)
-        os.replace(LIB + ".tmp", LIB)
+        for lib, sources in ((LIB, SOURCES), (PROBES_LIB, PROBE_SOURCES)):
+            objs = [os.path.join(tmp, obj) for _, obj, _ in sources]
+            _run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", lib + ".tmp", *objs], verbose)
+            os.replace(lib + ".tmp", lib)
     finally:
         shutil.rmtree(tmp, ignore_errors=True)
     return LIB

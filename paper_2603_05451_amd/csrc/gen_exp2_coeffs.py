@@ -1,5 +1,5 @@
 #!/usr/bin/env python3
-"""Prints the fp32 polynomial coefficients used by exp2_probe.hip.
+"""Prints the fp32 polynomial coefficients used by exp2_emulation.h.
 
 2^f on [0, 1) is approximated by 1 + p1 f + ... + pn f^n with the maximum RELATIVE error
 minimised and p0 fixed to 1 (paper Sec. 3.1.3 states the criterion; it prints no coefficients).

@@ -18,10 +18,10 @@ def L():
     return A.lib()
 
 
-def declared_functions():
-    text = open(os.path.join(ROOT, "include", "attn.h")).read()
+def declared_functions(header="attn.h"):
+    text = open(os.path.join(ROOT, "include", header)).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(attn_[a-z_]+)\s*\(", text)))
+    return sorted(set(re.findall(r"\b(attn_[a-z0-9_]+)\s*\(", text)))
 
 
 def test_every_declared_symbol_is_exported(L):
@@ -30,6 +30,21 @@ def test_every_declared_symbol_is_exported(L):
             "attn_bwd_workspace_bytes", "attn_strerror", "attn_version"} <= set(names)
     for n in names:
         assert hasattr(L, n), f"libattn.so does not export {n}"
+
+
+def test_every_declared_probe_is_exported_by_the_probe_library_only(L):
+    """include/attn_probes.h belongs to libattn_probes.so; the attention library ships none of it."""
+    from paper_2603_05451_amd import probes
+    if not os.path.exists(probes.LIB_PATH):
+        from paper_2603_05451_amd import build
+        build.build_library()
+    P = probes.lib()
+    names = declared_functions("attn_probes.h")
+    assert {"attn_exp2_rate", "attn_mfma_rate", "attn_lds_rate", "attn_probe_wave_issue"} <= set(names)
+    for n in names:
+        assert hasattr(P, n), f"libattn_probes.so does not export {n}"
+        assert not hasattr(L, n), f"libattn.so exports the probe {n}"
+    assert probes.wave_issue_configs()[0] == (0, 0, 0, 0, 4)      # host-side table, no GPU needed
 
 
 def test_version_and_error_strings(L):

@@ -1,4 +1,6 @@
-"""GPU software-exp2 (paper Sec. 3.1.3) against the numpy oracle and the paper's accuracy table."""
+"""GPU software-exp2 (paper Sec. 3.1.3) against the numpy oracle and the paper's accuracy table; the
+measurement probes of libattn_probes.so (rates of the exponential, the matrix cores, the LDS, and what
+the instructions around an MFMA cost a wave that is alone on its SIMD)."""
 import os
 
 import numpy as np
@@ -54,7 +56,7 @@ def test_hardware_exp2_matches_table_row():
 def test_emulation_is_slower_than_the_hardware_instruction(capsys):
     """The measurement behind keeping emulation off the path: evaluations per second of each
     variant, pure ALU, whole chip."""
-    import paper_2603_05451_amd as A
+    from paper_2603_05451_amd import probes as A
     rates = {}
     for degree in (0, 3, 4, 5):
         A.attn_exp2_rate(degree, 64)
@@ -76,7 +78,7 @@ def test_emulation_is_slower_than_the_hardware_instruction(capsys):
 def test_partial_emulation_lowers_the_exponential_rate():
     """Paper Sec. 3.1.3 runs 10-25 % of a row's exponentials on the FMA pipes next to the hardware
     unit.  Here both issue from one vector port: every share of emulation lowers the total rate."""
-    import paper_2603_05451_amd as A
+    from paper_2603_05451_amd import probes as A
     rates = {}
     for emu in (0, 1, 2, 4, 8):
         A.attn_exp2_rate_partial(emu, 64)
@@ -98,7 +100,7 @@ def test_partial_emulation_lowers_the_exponential_rate():
 def test_matrix_core_ceiling_on_random_operands():
     """Pure-MFMA rate with constant and with N(0,1) operands: the second is the ceiling every bf16
     MFMA kernel on such data is bounded by (the power limit lowers the clock)."""
-    import paper_2603_05451_amd as A
+    from paper_2603_05451_amd import probes as A
     rates = {}
     for name, rnd in (("constant", 0), ("N(0,1)", 1)):
         A.attn_mfma_rate(rnd, 2000)
@@ -124,7 +126,7 @@ def test_lds_read_rate_in_the_kernels_access_patterns():
     """Bytes per clock and CU that the LDS delivers in the two read patterns of the attention
     kernels (swizzled tiles: no bank conflicts expected).  The forward kernel reads 32 KiB per
     wave and 64-key tile, i.e. about 55 bytes per clock and CU at its measured speed."""
-    import paper_2603_05451_amd as A
+    from paper_2603_05451_amd import probes as A
     rates = {}
     for name, pat in (("ds_read_b128, A-operand fragments", 0), ("ds_read_b64_tr_b16, transposed fragments", 1)):
         A.attn_lds_rate(pat, 200)
@@ -141,3 +143,26 @@ def test_lds_read_rate_in_the_kernels_access_patterns():
     with open(path, "w") as f:
         f.write("\n".join(f"{k} : {v:.0f} B/clk/CU (at 2.4 GHz)" for k, v in rates.items()) + "\n")
     assert all(100 < v < 300 for v in rates.values())
+
+
+def test_single_wave_issue_costs():
+    """What accompanies an MFMA in a wave that is alone on its SIMD (the forward, dQ and dK/dV kernels
+    of the target shape): shader cycles per step, the clock the power limit leaves, and the whole-chip
+    rate, for every built variant.  Written to gpurun_out/wave_issue.txt; the assertions pin the
+    facts the kernel designs rest on."""
+    from paper_2603_05451_amd import probes as P
+    rows = {}
+    for c, cfg in enumerate(P.wave_issue_configs()):
+        rows[cfg] = P.wave_issue(c, 4000)
+    path = os.path.join(os.path.dirname(os.path.dirname(__file__)), "gpurun_out", "wave_issue.txt")
+    os.makedirs(os.path.dirname(path), exist_ok=True)
+    with open(path, "w") as f:
+        f.write("per step: 1 MFMA + ...                                   cycles/step  clock MHz  TFLOP/s\n")
+        for (nv, nb, ntr, dma, ring), (cyc, mhz, tf) in rows.items():
+            f.write(f"VALU {nv}  ds_read_b128 {nb}  tr pairs {ntr}  copy every {dma:2d}  ring {ring} : {cyc:8.1f} {mhz:10.0f} {tf:8.0f}\n")
+    alone = rows[(0, 0, 0, 0, 4)]
+    assert 31.5 < alone[0] < 35.0                                   # an MFMA of 8 passes every 32 cycles
+    assert rows[(0, 1, 0, 0, 4)][0] < 40.0                          # one 16-byte LDS fragment per MFMA still (nearly) fits
+    assert rows[(0, 2, 0, 0, 4)][0] > 45.0                          # two do not: LDS bandwidth
+    assert rows[(0, 0, 0, 1, 4)][0] > 55.0                          # a copy instruction per MFMA: the copy path
+    assert rows[(3, 0, 1, 0, 4)][2] < alone[2]                      # and everything costs clock or cycles
