@@ -77,16 +77,19 @@ namespace f16k {
 #if !ATTN_BWD_VGPR_FORM_PART
 int launch_bwd(const BwdArgs& a)
 {
-    // d = 128, fixed length, no mask: both passes have a kernel with one wave per SIMD of their own
-    // (attn_bwd_dq_q64.hip, attn_bwd_dkdv_u.hip), bit-identical to the kernels of this file and faster.
+    // d = 128, fixed length: both passes have a kernel with one wave per SIMD of their own
+    // (attn_bwd_dq_q64.hip; attn_bwd_dkdv_u.hip, without a mask only), faster than the kernels of this
+    // file and bit-identical to them up to the fp32 rounding of dP - D in the dQ kernel.
     // The dQ kernel, and with it -D and the base-2 LSE, comes first as in every backward call.
     auto generic = [&](int phases) {
         BwdArgs part = a;
         part.phases = phases;
         return a.f16 ? f16k::launch_bwd_dims(part) : launch_bwd_dims(part);
     };
-    const bool plain128 = !a.plan && !a.causal && a.d_qk == 128 && a.d_v == 128;
-    const bool dq_q64 = (a.phases & 4) && plain128 && a.N % 256 == 0 && a.N >= 1024;   // shorter: the 4-wave kernel wins
+    const bool fixed128 = !a.plan && a.d_qk == 128 && a.d_v == 128;
+    const bool plain128 = fixed128 && !a.causal;
+    // below these lengths the 4-wave kernel wins (its blocks are half the size and fill the chip better)
+    const bool dq_q64 = (a.phases & 4) && fixed128 && a.N % 256 == 0 && a.N >= (a.causal ? 4096 : 1024);
     const bool dkdv_u = (a.phases & 2) && plain128 && a.N % 128 == 0;
     if (!dq_q64 && !dkdv_u) return generic(a.phases);
     if (dq_q64) {

@@ -45,7 +45,7 @@ def test_offsets_beyond_32_bits(oracle):
     # the same data as a packed batch of 33 equal sequences: the variable-length kernels, with their
     # own offset arithmetic.  Forward: the packed call runs 128-query blocks, attn_fwd at this length
     # the kernel with 64 queries per wave (another summation order): one bf16 ulp.  Backward: the
-    # same kernels on the same tiles, from the same O and LSE: the same bits.
+    # same dK/dV kernel on the same tiles, from the same O and LSE: the same bits; dQ see below.
     del rdq, rdk, rdv, ro
     T = B * N
     cu = torch.arange(0, T + 1, N, dtype=torch.int32, device="cuda")
@@ -60,4 +60,10 @@ def test_offsets_beyond_32_bits(oracle):
     lse_packed = lse.permute(1, 0, 2).reshape(H, T).contiguous()
     gq, gk, gv = A.attn_varlen_bwd(p(q), p(k), p(v), p(o), p(do), lse_packed, cu, scale, causal)
     torch.cuda.synchronize()
-    assert torch.equal(gq, p(dq)) and torch.equal(gk, p(dk)) and torch.equal(gv, p(dv))
+    assert torch.equal(gk, p(dk)) and torch.equal(gv, p(dv))
+    # dQ: attn_bwd runs the kernel with 64 queries per wave at this length, whose dP accumulators start from
+    # -D (fp32 rounding of dP - D, i.e. now and then one ulp of a dS element): compared in slices to bound
+    # the memory of the float copies
+    for lo in range(0, T, T // 33):
+        a, b_ = gq[lo:lo + T // 33].float(), p(dq)[lo:lo + T // 33].float()
+        assert ((a - b_).abs() <= 2.0 ** -7 * torch.maximum(a.abs(), b_.abs()) + 2e-3).all()
