@@ -39,7 +39,8 @@ def test_gpu_emulation_matches_oracle_and_table(degree):
     e32 = np.abs(y[:1 << 22].astype(np.float64) - true) / true
     e16 = np.abs(E.to_bf16(y[:1 << 22]).astype(np.float64) - true) / true
     assert abs(e32.mean() - want[1]) <= 0.05 * want[1]
-    assert abs(e32.max() - want[0]) <= (0.5 if degree == 5 else 0.10) * want[0]
+    # degree 5: the fp32 Horner chain gives 2.1e-7 where the table prints 1.44e-7 (see tests/test_oracle_exp2.py)
+    assert abs(e32.max() - (2.08e-7 if degree == 5 else want[0])) <= 0.10 * (2.08e-7 if degree == 5 else want[0])
     assert abs(e16.max() - want[2]) <= 0.02 * want[2] and abs(e16.mean() - want[3]) <= 0.02 * want[3]
 
 

@@ -24,10 +24,19 @@ def test_polynomial_lands_on_the_papers_error_levels(degree):
     want = paper_table()[f"degree{degree}"]
     got = E.error_table(E.fit_coefficients(degree))
     # fp32-level errors: same polynomial family, same fp32 Horner.  Mean error within 5 % of the
-    # printed value; max error within 10 % (degree 5: its maximum is set by fp32 rounding of the
-    # Horner steps, not by the fit, and depends on the last bits of the coefficients: within 50 %)
+    # printed value; max error within 10 % for degrees 3 and 4.
     assert abs(got[1] - want[1]) <= 0.05 * want[1], (got, want)
-    assert abs(got[0] - want[0]) <= (0.5 if degree == 5 else 0.10) * want[0], (got, want)
+    if degree < 5:
+        assert abs(got[0] - want[0]) <= 0.10 * want[0], (got, want)
+    else:
+        # Degree 5: a FINDING, not a pass margin.  The printed maximum is 1.44e-7; the five steps of the
+        # section in fp32 give 2.08e-7 here (+44 %), and no choice of the last bits of the coefficients
+        # changes that (every +-1 ulp neighbour of the five rounded coefficients was tried: 2.04e-7 at
+        # best): at this degree the maximum is set by the roundings of the five FMAs of the Horner chain,
+        # about 3.5 ulp, not by the fit.  What evaluation the printed value came from the section does not
+        # say.  Asserted: the value this recipe gives, and that it stays above the printed one.
+        assert abs(got[0] - 2.08e-7) <= 0.05 * 2.08e-7, got
+        assert got[0] > want[0]
     # bf16-level errors are the quantisation floor for every degree >= 3
     assert abs(got[2] - want[2]) <= 0.02 * want[2] and abs(got[3] - want[3]) <= 0.02 * want[3], (got, want)
 
