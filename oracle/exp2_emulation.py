@@ -6,7 +6,9 @@ relative error on [0, 1) (the authors used Sollya; the coefficients are not prin
 evaluation with FMAs, and the integer part added into the exponent field.
 
 fit_coefficients(n) derives the polynomial from that statement alone: a linear program
-    minimise t  subject to  |1 + sum_{i>=1} p_i x^i - 2^x| <= t 2^x   on a Chebyshev grid of [0, 1].
+    minimise t  subject to  |1 + sum_{i>=1} p_i x^i - 2^x| <= t 2^x   on a Chebyshev grid of [0, 1],
+with its rows scaled by 1e4 so that the solver's feasibility tolerance (1e-7 in absolute terms, the
+size of the degree-5 error itself) is far below the error being minimised.
 exp2_emulated(x, coeffs) then takes the section's five steps in order, in fp32:
   1. clamp x to >= -127;
   2. floor(x)  (the section adds and subtracts 2^23 + 2^22 in round-down mode; np.floor is the
@@ -23,15 +25,18 @@ import numpy as np
 from scipy.optimize import linprog
 
 
+ROW_SCALE = 1e4     # the unknown t is the relative error in units of 1 / ROW_SCALE
+
+
 def fit_coefficients(degree: int, grid: int = 4001):
     """Minimax-relative-error coefficients p_1..p_degree (p_0 = 1) as fp64."""
     x = 0.5 + 0.5 * np.cos(np.pi * (np.arange(grid) + 0.5) / grid)
     f = 2.0 ** x
-    A = np.stack([x ** i for i in range(1, degree + 1)], axis=1)
+    A = ROW_SCALE * np.stack([x ** i for i in range(1, degree + 1)], axis=1)
     c = np.zeros(degree + 1)
     c[-1] = 1.0
     A_ub = np.vstack([np.hstack([A, -f[:, None]]), np.hstack([-A, -f[:, None]])])
-    b_ub = np.concatenate([f - 1.0, -(f - 1.0)])
+    b_ub = ROW_SCALE * np.concatenate([f - 1.0, -(f - 1.0)])
     res = linprog(c, A_ub=A_ub, b_ub=b_ub, bounds=[(None, None)] * degree + [(0, None)], method="highs")
     if not res.success:
         raise RuntimeError("minimax fit failed")

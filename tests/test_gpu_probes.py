@@ -30,7 +30,7 @@ def test_gpu_emulation_matches_oracle_and_table(degree):
     # the oracle's coefficients come from a linear program, the kernel's from a Remez exchange:
     # the two fits agree to the last fp32 digit or two, so results agree within a few ulp
     rel = np.abs(y.astype(np.float64) - ref.astype(np.float64)) / np.maximum(np.abs(ref), 1e-37)
-    assert rel.max() <= (1e-6 if degree < 5 else 2e-7 * 5), rel.max()
+    assert rel.max() <= 1e-6, rel.max()
     assert y[-7] == 0.0 and y[-6] == 0.0 and y[-3] == 1.0 and y[-2] == 2.0 and y[-1] == 131072.0
     # and the GPU result reproduces the paper's error levels on [0, 1)
     want = table()[f"degree{degree}"]
@@ -39,8 +39,7 @@ def test_gpu_emulation_matches_oracle_and_table(degree):
     e32 = np.abs(y[:1 << 22].astype(np.float64) - true) / true
     e16 = np.abs(E.to_bf16(y[:1 << 22]).astype(np.float64) - true) / true
     assert abs(e32.mean() - want[1]) <= 0.05 * want[1]
-    # degree 5: the fp32 Horner chain gives 2.1e-7 where the table prints 1.44e-7 (see tests/test_oracle_exp2.py)
-    assert abs(e32.max() - (2.08e-7 if degree == 5 else want[0])) <= 0.10 * (2.08e-7 if degree == 5 else want[0])
+    assert abs(e32.max() - want[0]) <= 0.10 * want[0]
     assert abs(e16.max() - want[2]) <= 0.02 * want[2] and abs(e16.mean() - want[3]) <= 0.02 * want[3]
 
 
