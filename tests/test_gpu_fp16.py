@@ -19,6 +19,9 @@ CASES = [
     I.Workload("h_d128_c_gqa", 2, 4, 1, 384, 128, 128, True, 63),
     I.Workload("h_d192_c", 1, 2, 2, 384, 192, 128, True, 64),
     I.Workload("h_d256_c", 1, 2, 1, 256, 256, 256, True, 67),
+    # shapes that run the one-wave-per-SIMD kernels (64 queries per wave forward and dQ, one-wave dK/dV)
+    I.Workload("h_d128_nc_2048_gqa", 1, 2, 1, 2048, 128, 128, False, 68),
+    I.Workload("h_d128_c_4096", 1, 1, 1, 4096, 128, 128, True, 69),
 ]
 
 
@@ -46,6 +49,19 @@ def test_fp16_fwd_bwd_parity(oracle, w):
     assert_close(n64(dk), rdk, f"fp16 dK {w.name}")
     assert_close(n64(dv), rdv, f"fp16 dV {w.name}")
     assert rf_o <= 1e-3, rf_o          # bf16 sits at 2.3e-3 (its output rounding floor); fp16 is 8x finer
+
+
+def test_fp16_fwd_d64_64_queries_per_wave(oracle):
+    """d = 64, N = 8192 without a mask: the forward kernel with 64 queries per wave in its fp16 form."""
+    import paper_2603_05451_amd as A
+    w = I.Workload("h_d64_nc_8192", 1, 2, 1, 8192, 64, 64, False, 70)
+    x = half_inputs(w)
+    o, lse = A.attn_fwd(x["q"].cuda(), x["k"].cuda(), x["v"].cuda(), w.scale, w.causal)
+    torch.cuda.synchronize()
+    ro, rlse = oracle.attn_fwd(I.to_f64(x["q"]), I.to_f64(x["k"]), I.to_f64(x["v"]), w.scale, w.causal)
+    _, rf_o = assert_close(o.float().cpu().numpy(), ro, f"fp16 O {w.name}")
+    assert np.abs(lse.cpu().numpy() - rlse).max() <= LSE_ABS
+    assert rf_o <= 1e-3, rf_o
 
 
 def test_fp16_varlen_parity(oracle):
