@@ -232,11 +232,12 @@ def main():
     dkdv_name = ("attn_bwd_dkdv_u_kernel" if w.dqk == 128 and not w.causal else
                  "attn_bwd_dkdv_ws_kernel" if w.dqk in (96, 128) else "attn_bwd_dkdv_kernel")
     # on long sequences with N % 256 == 0 the library runs 256-query blocks with 64 queries per wave:
-    # the forward kernel at d = 128 and d = 64, the dQ kernel at d = 128 (same rules as the launchers)
+    # the forward and dQ kernels at d = 128 and d = 64 (same rules as the launchers)
     wide = w.dqk == 128 and w.dv == 128 and w.N % 256 == 0
     fwd_name = ("attn_fwd_q64_kernel" if (wide and w.N >= (8192 if w.causal else 2048)) or
                 (w.dqk == 64 and w.dv == 64 and w.N % 256 == 0 and w.N >= (16384 if w.causal else 8192)) else "attn_fwd_kernel")
-    dq_name = "attn_bwd_dq_q64_kernel" if wide and w.N >= (4096 if w.causal else 1024) else "attn_bwd_dq_kernel"
+    dq_name = ("attn_bwd_dq_q64_kernel" if (wide and w.N >= (4096 if w.causal else 1024)) or
+               (w.dqk == 64 and w.dv == 64 and w.N % 256 == 0 and w.N >= (8192 if w.causal else 2048)) else "attn_bwd_dq_kernel")
     # the dQ kernel computes D and the base-2 LSE itself: the full backward launches no prepare kernel
     # (ATTN_BWD_PREPARE alone still does, which is what ms_prep timed above)
     ms_prep_alone, ms_prep = ms_prep, 0.0

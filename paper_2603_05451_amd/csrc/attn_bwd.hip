@@ -78,7 +78,7 @@ namespace f16k {
 int launch_bwd(const BwdArgs& a)
 {
     // d = 128, fixed length: both passes have a kernel with one wave per SIMD of their own
-    // (attn_bwd_dq_q64.hip; attn_bwd_dkdv_u.hip, without a mask only), faster than the kernels of this
+    // (attn_bwd_dq_q64.hip, which also serves d = 64; attn_bwd_dkdv_u.hip, without a mask only), faster than the kernels of this
     // file and bit-identical to them up to the fp32 rounding of dP - D in the dQ kernel.
     // The dQ kernel, and with it -D and the base-2 LSE, comes first as in every backward call.
     auto generic = [&](int phases) {
@@ -88,8 +88,10 @@ int launch_bwd(const BwdArgs& a)
     };
     const bool fixed128 = !a.plan && a.d_qk == 128 && a.d_v == 128;
     const bool plain128 = fixed128 && !a.causal;
-    // below these lengths the 4-wave kernel wins (its blocks are half the size and fill the chip better)
-    const bool dq_q64 = (a.phases & 4) && fixed128 && a.N % 256 == 0 && a.N >= (a.causal ? 4096 : 1024);
+    const bool fixed64 = !a.plan && a.d_qk == 64 && a.d_v == 64;
+    // below these lengths the 4-wave kernels win (their blocks are half the size and fill the chip better)
+    const bool dq_q64 = (a.phases & 4) && a.N % 256 == 0 &&
+                        ((fixed128 && a.N >= (a.causal ? 4096 : 1024)) || (fixed64 && a.N >= (a.causal ? 8192 : 2048)));
     const bool dkdv_u = (a.phases & 2) && plain128 && a.N % 128 == 0;
     if (!dq_q64 && !dkdv_u) return generic(a.phases);
     if (dq_q64) {

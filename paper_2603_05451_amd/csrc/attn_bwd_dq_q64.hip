@@ -1,5 +1,5 @@
-// dQ kernel of the backward pass at head dim 128 with 64 queries per wave (gfx950): fixed-length
-// batches without a mask.  What is computed is described in attn_bwd.hip; how, at the top of
+// dQ kernel of the backward pass at head dims 128 and 64 with 64 queries per wave (gfx950): long
+// fixed-length batches, with or without the causal mask.  What is computed is described in attn_bwd.hip; how, at the top of
 // attn_bwd_dq_q64_kernel.inc.  A translation unit of its own, like attn_fwd_q64.hip, whose
 // techniques it shares.
 #include "common.h"

@@ -158,14 +158,15 @@ def test_literal_north_star_entry_points_on_live_tensors():
         assert torch.equal(a, b)
 
 
-@pytest.mark.parametrize("causal", [True, False])
-def test_dq_of_every_row_of_the_first_and_last_query_tiles(oracle, causal):
-    """d = 128, N = 4096: the dQ kernel with 64 queries per wave.  Every row of the first two and of the
+@pytest.mark.parametrize("causal,d,N", [(True, 128, 4096), (False, 128, 4096), (True, 64, 8192), (False, 64, 2048)])
+def test_dq_of_every_row_of_the_first_and_last_query_tiles(oracle, causal, d, N):
+    """The dQ kernel with 64 queries per wave at its shortest sequences (d = 128: N = 4096; d = 64: N = 8192
+    with the causal mask, 2048 without).  Every row of the first two and of the
     last two 256-query tiles of one (batch, head) against the oracle: under the causal mask the first
     tiles have the shortest rows and the largest P, so one wrong (query, key) pair of the last key block
     of a tile shows there and nowhere else (sampled rows of long sequences do not see it)."""
     import paper_2603_05451_amd as A
-    w = I.Workload("dq_tiles", 1, 4, 2, 4096, 128, 128, causal, 73)
+    w = I.Workload("dq_tiles", 1, 4, 2, N, d, d, causal, 73)
     x = I.make_inputs(w)
     q, k, v, do = (x[n].cuda() for n in ("q", "k", "v", "do"))
     o, lse = A.attn_fwd(q, k, v, w.scale, causal)
@@ -175,7 +176,7 @@ def test_dq_of_every_row_of_the_first_and_last_query_tiles(oracle, causal):
     f = lambda name, r=slice(None), h=3: I.to_f64(x[name][0, r, h])[None, :, None, :]
     rdq, _, _ = oracle.attn_bwd(f("q", rows), f("k", h=1), f("v", h=1), f("do", rows), w.scale, causal, q_pos=rows)
     got = dq[0, torch.from_numpy(rows).cuda(), 3].float().cpu().numpy()[None, :, None, :]
-    assert_close(got, rdq, f"dQ all rows of four tiles, causal={causal}")
+    assert_close(got, rdq, f"dQ all rows of four tiles, causal={causal} d={d}")
     # row by row as well: an error confined to a few rows must not hide in the norm of a thousand
     err = np.abs(got - rdq)[0, :, 0].max(axis=1)
     assert (err <= 2e-3 + 2.0 ** -8 * np.abs(rdq)[0, :, 0].max(axis=1)).all(), (rows[err.argmax()], err.max())

@@ -22,6 +22,7 @@ CASES = [
     # shapes that run the one-wave-per-SIMD kernels (64 queries per wave forward and dQ, one-wave dK/dV)
     I.Workload("h_d128_nc_2048_gqa", 1, 2, 1, 2048, 128, 128, False, 68),
     I.Workload("h_d128_c_4096", 1, 1, 1, 4096, 128, 128, True, 69),
+    I.Workload("h_d64_nc_2048", 1, 2, 1, 2048, 64, 64, False, 71),
 ]
 
 
