@@ -230,6 +230,7 @@ def main():
     f_dq = 2.0 * pairs * (2 * w.dqk + w.dv)           # S, dQ over d_qk; dP over d_v
     tf = lambda flops, ms: flops / ms / 1e9
     dkdv_name = ("attn_bwd_dkdv_u_kernel" if w.dqk == 128 and not w.causal else
+                 "attn_bwd_dkdv_k64_kernel" if w.dqk == 64 and w.dv == 64 and not w.causal and w.N % 256 == 0 and w.N >= 2048 else
                  "attn_bwd_dkdv_ws_kernel" if w.dqk in (96, 128) else "attn_bwd_dkdv_kernel")
     # on long sequences with N % 256 == 0 the library runs 256-query blocks with 64 queries per wave:
     # the forward and dQ kernels at d = 128 and d = 64 (same rules as the launchers)

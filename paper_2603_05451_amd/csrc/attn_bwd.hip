@@ -79,7 +79,8 @@ int launch_bwd(const BwdArgs& a)
 {
     // d = 128, fixed length: both passes have a kernel with one wave per SIMD of their own
     // (attn_bwd_dq_q64.hip, which also serves d = 64; attn_bwd_dkdv_u.hip, without a mask only), faster than the kernels of this
-    // file and bit-identical to them up to the fp32 rounding of dP - D in the dQ kernel.
+    // file and bit-identical to them up to the fp32 rounding of dP - D in the dQ kernel.  d = 64 without a mask
+    // has a dK/dV kernel with 64 keys per wave (attn_bwd_dkdv_k64_kernel.inc), bit-identical as well.
     // The dQ kernel, and with it -D and the base-2 LSE, comes first as in every backward call.
     auto generic = [&](int phases) {
         BwdArgs part = a;
@@ -93,13 +94,15 @@ int launch_bwd(const BwdArgs& a)
     const bool dq_q64 = (a.phases & 4) && a.N % 256 == 0 &&
                         ((fixed128 && a.N >= (a.causal ? 4096 : 1024)) || (fixed64 && a.N >= (a.causal ? 8192 : 2048)));
     const bool dkdv_u = (a.phases & 2) && plain128 && a.N % 128 == 0;
-    if (!dq_q64 && !dkdv_u) return generic(a.phases);
+    const bool dkdv_k64 = (a.phases & 2) && fixed64 && !a.causal && a.N % 256 == 0 && a.N >= 2048;
+    if (!dq_q64 && !dkdv_u && !dkdv_k64) return generic(a.phases);
     if (dq_q64) {
         if (const int rc = launch_bwd_dq_q64(a)) return rc;
     } else if (a.phases & 5) {
         if (const int rc = generic(a.phases & 5)) return rc;
     }
     if (dkdv_u) return launch_bwd_dkdv_u(a);
+    if (dkdv_k64) return launch_bwd_dkdv_k64(a);
     return (a.phases & 2) ? generic(2) : 0;
 }
 #endif

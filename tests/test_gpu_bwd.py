@@ -34,6 +34,10 @@ SMALL = [
     I.Workload("s_d192_c", 1, 4, 2, 384, 192, 128, True, 25),
     I.Workload("s_d192_nc", 1, 2, 2, 256, 192, 128, False, 26),
     I.Workload("s_d192_c_outl", 1, 2, 1, 512, 192, 128, True, 27, outlier_frac=0.01),
+    # d = 64 without a mask from N = 2048: the one-wave-per-SIMD kernels (64 queries per wave for dQ, 64 keys
+    # per wave for dK / dV), GQA with three heads per group, 8 and 9 blocks of 256 rows
+    I.Workload("s_d64_nc_2048_gqa", 1, 3, 1, 2048, 64, 64, False, 18),
+    I.Workload("s_d64_nc_2304", 2, 2, 2, 2304, 64, 64, False, 17),
 ]
 
 
