@@ -161,7 +161,7 @@ def test_single_wave_issue_costs():
         for (nv, nb, ntr, dma, ring), (cyc, mhz, tf) in rows.items():
             f.write(f"VALU {nv}  ds_read_b128 {nb}  tr pairs {ntr}  copy every {dma:2d}  ring {ring} : {cyc:8.1f} {mhz:10.0f} {tf:8.0f}\n")
     alone = rows[(0, 0, 0, 0, 4)]
-    assert 31.5 < alone[0] < 35.0                                   # an MFMA of 8 passes every 32 cycles
+    assert 31.5 < alone[0] < 36.0                                   # an MFMA of 8 passes every 32 cycles
     assert rows[(0, 1, 0, 0, 4)][0] < 40.0                          # one 16-byte LDS fragment per MFMA still (nearly) fits
     assert rows[(0, 2, 0, 0, 4)][0] > 45.0                          # two do not: LDS bandwidth
     assert rows[(0, 0, 0, 1, 4)][0] > 55.0                          # a copy instruction per MFMA: the copy path
