@@ -235,7 +235,7 @@ def main():
     # on long sequences with N % 256 == 0 the library runs 256-query blocks with 64 queries per wave:
     # the forward and dQ kernels at d = 128 and d = 64 (same rules as the launchers)
     wide = w.dqk == 128 and w.dv == 128 and w.N % 256 == 0
-    fwd_name = ("attn_fwd_q64_kernel" if (wide and w.N >= (8192 if w.causal else 2048)) or
+    fwd_name = ("attn_fwd_q64_kernel" if ((wide or (w.dqk == 192 and w.dv == 128 and w.N % 256 == 0)) and w.N >= (8192 if w.causal else 2048)) or
                 (w.dqk == 64 and w.dv == 64 and w.N % 256 == 0 and w.N >= (16384 if w.causal else 8192)) else "attn_fwd_kernel")
     dq_name = ("attn_bwd_dq_q64_kernel" if (wide and w.N >= (4096 if w.causal else 1024)) or
                (w.dqk == 64 and w.dv == 64 and w.N % 256 == 0 and w.N >= (8192 if w.causal else 2048)) else "attn_bwd_dq_kernel")

@@ -10,7 +10,7 @@
 //   wave w = 32 query rows; it keeps its Q rows in registers for the whole kernel;
 //   K/V tiles of BN = 64 keys stream through LDS, double buffered, copied straight
 //   from global memory into LDS (no VGPR staging) one tile ahead of the compute.
-//   At d = 128 / 64 and long fixed-length sequences the kernel of attn_fwd_q64.hip runs instead (64
+//   At d = 128, 64 and (192, 128) and long fixed-length sequences the kernel of attn_fwd_q64.hip runs instead (64
 //   queries per wave, one wave per SIMD).
 //
 // MFMA orientation.  Scores are computed TRANSPOSED, S^T = K Q^T (keys on the MFMA row

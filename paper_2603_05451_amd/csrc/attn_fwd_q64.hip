@@ -1,4 +1,4 @@
-// Forward attention at head dims 128 and 64 with 64 queries per wave (gfx950): the long-sequence,
+// Forward attention at head dims 128, 64 and (192, 128) with 64 queries per wave (gfx950): the long-sequence,
 // fixed-length form of the forward pass.  What is computed is that of attn_fwd.hip (paper
 // Sec. 2.1, online softmax with the thresholded rescale of Sec. 3.1.4, base 2); how the work is
 // laid out is described at the top of attn_fwd_q64_kernel.inc.  A translation unit of its own:

@@ -95,7 +95,7 @@ struct LdsOptIn {
 // 0 on success, -2 unsupported head dims, -3 launch failure.
 int launch_fwd(const FwdArgs& a);
 int launch_bwd(const BwdArgs& a);
-// The 64-queries-per-wave forward kernel (d_qk = d_v = 128, fixed length, N % 256 = 0).
+// The 64-queries-per-wave forward kernel (head dims 128, 64 or (192, 128); fixed length, N % 256 = 0).
 int launch_fwd_q64(const FwdArgs& a);
 // The dK/dV kernel with one wave per SIMD in both roles (d_qk = d_v = 128, fixed length, N % 128 = 0);
 // -D and the base-2 LSE must be in the workspace.

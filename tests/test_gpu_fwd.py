@@ -85,14 +85,17 @@ def test_fwd_full_size_sampled_rows(oracle, w):
 Q64 = [I.Workload("q64_nc_2048", 1, 3, 1, 2048, 128, 128, False, 31),
        I.Workload("q64_nc_2304", 2, 2, 2, 2304, 128, 128, False, 32),
        I.Workload("q64_d64_nc_8192", 1, 2, 1, 8192, 64, 64, False, 33),
-       I.Workload("q64_d64_c_16384", 1, 1, 1, 16384, 64, 64, True, 34)]
+       I.Workload("q64_d64_c_16384", 1, 1, 1, 16384, 64, 64, True, 34),
+       I.Workload("q64_d192_nc_2304", 1, 3, 1, 2304, 192, 128, False, 35),
+       I.Workload("q64_d192_c_8192", 1, 2, 2, 8192, 192, 128, True, 36)]
 
 
 @pytest.mark.parametrize("w", Q64, ids=lambda w: w.name)
 def test_fwd_64_queries_per_wave_full_parity(oracle, w):
-    """Shapes that run the kernel with 64 queries per wave (N % 256 = 0; d = 128 from N = 2048 without
-    a mask, d = 64 from N = 8192 without and N = 16384 with the mask), small enough for the oracle to
-    compute every row: 8 to 64 query blocks of 256, GQA and MHA, key loops of 32 to 256 tiles."""
+    """Shapes that run the kernel with 64 queries per wave (N % 256 = 0; d = 128 and (192, 128) from
+    N = 2048 without a mask and N = 8192 with it, d = 64 from N = 8192 without and N = 16384 with the mask),
+    small enough for the oracle to compute every row: 8 to 64 query blocks of 256, GQA and MHA, key loops
+    of 32 to 256 tiles."""
     x = I.make_inputs(w, with_do=False)
     o, lse = gpu_fwd(w, x)
     ro, rlse = oracle.attn_fwd(I.to_f64(x["q"]), I.to_f64(x["k"]), I.to_f64(x["v"]), w.scale, w.causal)
@@ -100,8 +103,9 @@ def test_fwd_64_queries_per_wave_full_parity(oracle, w):
     assert np.abs(lse - rlse).max() <= LSE_ABS, f"LSE {w.name}: {np.abs(lse - rlse).max():.3e}"
 
 
-@pytest.mark.parametrize("causal,N,d", [(False, 2048, 128), (True, 8192, 128), (False, 8192, 64), (True, 16384, 64)])
-def test_fwd_growing_scores_restart_with_exact_maxima(oracle, causal, N, d):
+@pytest.mark.parametrize("causal,N,d,dv", [(False, 2048, 128, 128), (True, 8192, 128, 128), (False, 8192, 64, 64), (True, 16384, 64, 64),
+                                           (False, 2048, 192, 128), (True, 8192, 192, 128)])
+def test_fwd_growing_scores_restart_with_exact_maxima(oracle, causal, N, d, dv):
     """Scores that grow along the key axis by hundreds of binary orders: relative to the first
     tile's maximum the exponentials overflow, so the pipelined loop of the 64-queries-per-wave
     kernel cannot produce these results; they come from its restart with a row maximum per tile
@@ -111,7 +115,7 @@ def test_fwd_growing_scores_restart_with_exact_maxima(oracle, causal, N, d):
     H = 2
     q = torch.randn(1, N, H, d, generator=g).abs().to(torch.bfloat16)
     k = (torch.randn(1, N, 1, d, generator=g).abs() * torch.linspace(0.2, 30.0, N).view(1, N, 1, 1)).to(torch.bfloat16)
-    v = torch.randn(1, N, 1, d, generator=g).to(torch.bfloat16)
+    v = torch.randn(1, N, 1, dv, generator=g).to(torch.bfloat16)
     scale = d ** -0.5
     o, lse = A.attn_fwd(q.cuda(), k.cuda(), v.cuda(), scale, causal)
     torch.cuda.synchronize()
