@@ -22,7 +22,7 @@ PEAK_BF16_TFLOPS = 2500.0      # MI355X published dense bf16 MFMA peak
 # --pmc runs, scaled by the same counters' reading for a 1 GiB copy; profiles/bench_target_*.md).
 # They cannot be measured from inside this process; None for any other workload.
 MEASURED_TRAFFIC = {
-    "target_N8192_d128_nc": {"attn_fwd_q64_kernel": 208e6 + 74e6, "attn_bwd_dkdv_u_kernel": 407e6 + 134e6,
+    "target_N8192_d128_nc": {"attn_fwd_q64_kernel": 208e6 + 74e6, "attn_bwd_dkdv_t32_kernel": 407e6 + 134e6,
                              "attn_bwd_dq_q64_kernel": 337e6 + 69e6},
 }
 PAPER_CONTEXT = "paper: up to 1613 TFLOP/s forward (71% of 2.25 PFLOP/s) on B200, BF16 -- other hardware, context only"
@@ -229,8 +229,9 @@ def main():
     f_dkdv = 2.0 * pairs * (2 * w.dqk + 2 * w.dv)     # S, dK contract/emit d_qk; dP, dV d_v
     f_dq = 2.0 * pairs * (2 * w.dqk + w.dv)           # S, dQ over d_qk; dP over d_v
     tf = lambda flops, ms: flops / ms / 1e9
-    dkdv_name = ("attn_bwd_dkdv_u_kernel" if w.dqk == 128 and not w.causal else
-                 "attn_bwd_dkdv_k64_kernel" if w.dqk == 64 and w.dv == 64 and not w.causal and w.N % 256 == 0 and w.N >= 2048 else
+    t32 = ((w.dqk, w.dv) in ((128, 128), (192, 128)) and w.N % 128 == 0) or \
+          ((w.dqk, w.dv) == (64, 64) and w.N % 256 == 0 and w.N >= (4096 if w.causal else 512))
+    dkdv_name = ("attn_bwd_dkdv_t32_kernel" if t32 else
                  "attn_bwd_dkdv_ws_kernel" if w.dqk in (96, 128) else "attn_bwd_dkdv_kernel")
     # on long sequences with N % 256 == 0 the library runs 256-query blocks with 64 queries per wave:
     # the forward and dQ kernels at d = 128 and d = 64 (same rules as the launchers)

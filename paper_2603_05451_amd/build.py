@@ -27,7 +27,6 @@ SOURCES = [("attn_api.hip", "attn_api.o", []),
            ("attn_fwd_q64.hip", "attn_fwd_q64.o", []),
            ("attn_bwd.hip", "attn_bwd.o", []),
            ("attn_bwd.hip", "attn_bwd_vgpr_form.o", ["-DATTN_BWD_VGPR_FORM_PART=1", *VGPR_FORM]),
-           ("attn_bwd_dkdv_u.hip", "attn_bwd_dkdv_u.o", []),
            ("attn_bwd_dq_q64.hip", "attn_bwd_dq_q64.o", []),
            ("attn_varlen.hip", "attn_varlen.o", []),
            ("exp2_emulated.hip", "exp2_emulated.o", [])]

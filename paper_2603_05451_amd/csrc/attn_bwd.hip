@@ -77,32 +77,29 @@ namespace f16k {
 #if !ATTN_BWD_VGPR_FORM_PART
 int launch_bwd(const BwdArgs& a)
 {
-    // d = 128, fixed length: both passes have a kernel with one wave per SIMD of their own
-    // (attn_bwd_dq_q64.hip, which also serves d = 64; attn_bwd_dkdv_u.hip, without a mask only), faster than the kernels of this
-    // file and bit-identical to them up to the fp32 rounding of dP - D in the dQ kernel.  d = 64 without a mask
-    // has a dK/dV kernel with 64 keys per wave (attn_bwd_dkdv_k64_kernel.inc), bit-identical as well.
-    // The dQ kernel, and with it -D and the base-2 LSE, comes first as in every backward call.
+    // Fixed-length batches at head dims 128, 64 and (192, 128): kernels with one wave per SIMD
+    // (attn_bwd_dq_q64.hip), faster than the kernels of this file.  The dK/dV kernel gives the same bits
+    // as they do; the dQ kernel differs by the fp32 rounding of dP - D.  The dQ kernel, and with it -D and
+    // the base-2 LSE, comes first as in every backward call.
     auto generic = [&](int phases) {
         BwdArgs part = a;
         part.phases = phases;
         return a.f16 ? f16k::launch_bwd_dims(part) : launch_bwd_dims(part);
     };
-    const bool fixed128 = !a.plan && a.d_qk == 128 && a.d_v == 128;
-    const bool plain128 = fixed128 && !a.causal;
-    const bool fixed64 = !a.plan && a.d_qk == 64 && a.d_v == 64;
-    // below these lengths the 4-wave kernels win (their blocks are half the size and fill the chip better)
-    const bool dq_q64 = (a.phases & 4) && a.N % 256 == 0 &&
-                        ((fixed128 && a.N >= (a.causal ? 4096 : 1024)) || (fixed64 && a.N >= (a.causal ? 8192 : 2048)));
-    const bool dkdv_u = (a.phases & 2) && plain128 && a.N % 128 == 0;
-    const bool dkdv_k64 = (a.phases & 2) && fixed64 && !a.causal && a.N % 256 == 0 && a.N >= 2048;
-    if (!dq_q64 && !dkdv_u && !dkdv_k64) return generic(a.phases);
+    const bool d128 = a.d_qk == 128 && a.d_v == 128, d64 = a.d_qk == 64 && a.d_v == 64, d192 = a.d_qk == 192 && a.d_v == 128;
+    // below these lengths the 4-wave dQ kernel wins (its blocks are half the size and fill the chip better);
+    // at d = 64 the 256-key blocks of the dK/dV kernel are too few on short sequences
+    const bool dq_q64 = (a.phases & 4) && !a.plan && a.N % 256 == 0 &&
+                        ((d128 && a.N >= (a.causal ? 4096 : 1024)) || (d64 && a.N >= (a.causal ? 8192 : 2048)));
+    const bool dkdv_t32 = (a.phases & 2) && !a.plan &&
+                          (((d128 || d192) && a.N % 128 == 0) || (d64 && a.N % 256 == 0 && a.N >= (a.causal ? 4096 : 512)));
+    if (!dq_q64 && !dkdv_t32) return generic(a.phases);
     if (dq_q64) {
         if (const int rc = launch_bwd_dq_q64(a)) return rc;
     } else if (a.phases & 5) {
         if (const int rc = generic(a.phases & 5)) return rc;
     }
-    if (dkdv_u) return launch_bwd_dkdv_u(a);
-    if (dkdv_k64) return launch_bwd_dkdv_k64(a);
+    if (dkdv_t32) return launch_bwd_dkdv_t32(a);
     return (a.phases & 2) ? generic(2) : 0;
 }
 #endif

@@ -1,8 +1,11 @@
-// dQ kernel of the backward pass at head dims 128 and 64 with 64 queries per wave (gfx950): long
-// fixed-length batches, with or without the causal mask; and the dK/dV kernel of head dim 64 with 64 keys
-// per wave (attn_bwd_dkdv_k64_kernel.inc), its dual.  What is computed is described in attn_bwd.hip; how, at the top of
-// attn_bwd_dq_q64_kernel.inc.  A translation unit of its own, like attn_fwd_q64.hip, whose
-// techniques it shares.
+// The backward kernels with one wave per SIMD (gfx950), fixed-length batches:
+//   attn_bwd_dq_q64_kernel    dQ with 64 queries per wave, head dims 128 and 64, long sequences, with or
+//                             without the causal mask (attn_bwd_dq_q64_kernel.inc);
+//   attn_bwd_dkdv_t32_kernel  dK / dV, its dual: K_w / V_w stationary, 32-query tiles of Q / dO streamed;
+//                             head dims 128, (192, 128) with 32 keys per wave and 64 with 64 keys per wave
+//                             (attn_bwd_dkdv_t32_kernel.inc).
+// What is computed is described in attn_bwd.hip; how, at the top of the two kernel files.  A translation
+// unit of its own, like attn_fwd_q64.hip, whose techniques it shares.
 #include "common.h"
 #include "launch.h"
 
@@ -18,7 +21,7 @@ namespace attn {
 #define ATTN_MFMA "v_mfma_f32_32x32x16_bf16"
 typedef bf16x2 elem2;
 #include "attn_bwd_dq_q64_kernel.inc"
-#include "attn_bwd_dkdv_k64_kernel.inc"
+#include "attn_bwd_dkdv_t32_kernel.inc"
 #undef ATTN_MFMA
 #include "attn_bwd_dq_q64_launch.inc"
 
@@ -33,12 +36,12 @@ namespace f16k {
 #define ATTN_MFMA "v_mfma_f32_32x32x16_f16"
 typedef __attribute__((ext_vector_type(2))) _Float16 elem2;
 #include "attn_bwd_dq_q64_kernel.inc"
-#include "attn_bwd_dkdv_k64_kernel.inc"
+#include "attn_bwd_dkdv_t32_kernel.inc"
 #undef ATTN_MFMA
 #include "attn_bwd_dq_q64_launch.inc"
 }  // namespace f16k
 
 int launch_bwd_dq_q64(const BwdArgs& a) { return a.f16 ? f16k::launch_bwd_dq_q64_t(a) : launch_bwd_dq_q64_t(a); }
-int launch_bwd_dkdv_k64(const BwdArgs& a) { return a.f16 ? f16k::launch_bwd_dkdv_k64_t(a) : launch_bwd_dkdv_k64_t(a); }
+int launch_bwd_dkdv_t32(const BwdArgs& a) { return a.f16 ? f16k::launch_bwd_dkdv_t32_t(a) : launch_bwd_dkdv_t32_t(a); }
 
 }  // namespace attn

@@ -97,15 +97,12 @@ int launch_fwd(const FwdArgs& a);
 int launch_bwd(const BwdArgs& a);
 // The 64-queries-per-wave forward kernel (head dims 128, 64 or (192, 128); fixed length, N % 256 = 0).
 int launch_fwd_q64(const FwdArgs& a);
-// The dK/dV kernel with one wave per SIMD in both roles (d_qk = d_v = 128, fixed length, N % 128 = 0);
-// -D and the base-2 LSE must be in the workspace.
-int launch_bwd_dkdv_u(const BwdArgs& a);
-// The dQ kernel with 64 queries per wave (d_qk = d_v = 128, fixed length, no mask, N % 256 = 0); it also
+// The dQ kernel with 64 queries per wave (d_qk = d_v = 128 or 64, fixed length, N % 256 = 0); it also
 // leaves -D and the base-2 LSE of every row in the workspace.
 int launch_bwd_dq_q64(const BwdArgs& a);
-// The dK/dV kernel with 64 keys per wave (d_qk = d_v = 64, fixed length, no mask, N % 256 = 0); -D and the
-// base-2 LSE must be in the workspace.
-int launch_bwd_dkdv_k64(const BwdArgs& a);
+// The dK/dV kernel with one wave per SIMD and 32-query tiles (head dims 128, (192, 128): N % 128 = 0; 64:
+// N % 256 = 0; fixed length, with or without the causal mask); -D and the base-2 LSE must be in the workspace.
+int launch_bwd_dkdv_t32(const BwdArgs& a);
 // cu[b] = b * N for b = 0 .. B (device): the equal-length batch as a packed one.
 int launch_uniform_cu(int* cu, int B, int N, void* stream);
 // Fills the two plan tables of the variable-length entry points on the device: 0 or -3.
