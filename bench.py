@@ -239,7 +239,9 @@ def main():
     fwd_name = ("attn_fwd_q64_kernel" if ((wide or (w.dqk == 192 and w.dv == 128 and w.N % 256 == 0)) and w.N >= (8192 if w.causal else 2048)) or
                 (w.dqk == 64 and w.dv == 64 and w.N % 256 == 0 and w.N >= (16384 if w.causal else 8192)) else "attn_fwd_kernel")
     dq_name = ("attn_bwd_dq_q64_kernel" if (wide and w.N >= (4096 if w.causal else 1024)) or
-               (w.dqk == 64 and w.dv == 64 and w.N % 256 == 0 and w.N >= (8192 if w.causal else 2048)) else "attn_bwd_dq_kernel")
+               (w.dqk == 64 and w.dv == 64 and w.N % 256 == 0 and w.N >= (8192 if w.causal else 2048)) else
+               "attn_bwd_dq_t32_kernel" if (w.dqk, w.dv) == (192, 128) and w.N % 128 == 0 and w.N >= (1024 if w.causal else 512) else
+               "attn_bwd_dq_kernel")
     # the dQ kernel computes D and the base-2 LSE itself: the full backward launches no prepare kernel
     # (ATTN_BWD_PREPARE alone still does, which is what ms_prep timed above)
     ms_prep_alone, ms_prep = ms_prep, 0.0

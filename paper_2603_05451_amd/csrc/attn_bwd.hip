@@ -93,9 +93,13 @@ int launch_bwd(const BwdArgs& a)
                         ((d128 && a.N >= (a.causal ? 4096 : 1024)) || (d64 && a.N >= (a.causal ? 8192 : 2048)));
     const bool dkdv_t32 = (a.phases & 2) && !a.plan &&
                           (((d128 || d192) && a.N % 128 == 0) || (d64 && a.N % 256 == 0 && a.N >= (a.causal ? 4096 : 512)));
-    if (!dq_q64 && !dkdv_t32) return generic(a.phases);
+    // (192, 128): the 64-query kernel's fragments and accumulators do not fit; 32 queries per wave, pipelined
+    const bool dq_t32 = (a.phases & 4) && !a.plan && d192 && a.N % 128 == 0 && a.N >= (a.causal ? 1024 : 512);
+    if (!dq_q64 && !dq_t32 && !dkdv_t32) return generic(a.phases);
     if (dq_q64) {
         if (const int rc = launch_bwd_dq_q64(a)) return rc;
+    } else if (dq_t32) {
+        if (const int rc = launch_bwd_dq_t32(a)) return rc;
     } else if (a.phases & 5) {
         if (const int rc = generic(a.phases & 5)) return rc;
     }

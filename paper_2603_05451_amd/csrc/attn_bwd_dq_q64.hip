@@ -22,6 +22,7 @@ namespace attn {
 typedef bf16x2 elem2;
 #include "attn_bwd_dq_q64_kernel.inc"
 #include "attn_bwd_dkdv_t32_kernel.inc"
+#include "attn_bwd_dq_t32_kernel.inc"
 #undef ATTN_MFMA
 #include "attn_bwd_dq_q64_launch.inc"
 
@@ -37,11 +38,13 @@ namespace f16k {
 typedef __attribute__((ext_vector_type(2))) _Float16 elem2;
 #include "attn_bwd_dq_q64_kernel.inc"
 #include "attn_bwd_dkdv_t32_kernel.inc"
+#include "attn_bwd_dq_t32_kernel.inc"
 #undef ATTN_MFMA
 #include "attn_bwd_dq_q64_launch.inc"
 }  // namespace f16k
 
 int launch_bwd_dq_q64(const BwdArgs& a) { return a.f16 ? f16k::launch_bwd_dq_q64_t(a) : launch_bwd_dq_q64_t(a); }
+int launch_bwd_dq_t32(const BwdArgs& a) { return a.f16 ? f16k::launch_bwd_dq_t32_t(a) : launch_bwd_dq_t32_t(a); }
 int launch_bwd_dkdv_t32(const BwdArgs& a) { return a.f16 ? f16k::launch_bwd_dkdv_t32_t(a) : launch_bwd_dkdv_t32_t(a); }
 
 }  // namespace attn

@@ -103,6 +103,9 @@ int launch_bwd_dq_q64(const BwdArgs& a);
 // The dK/dV kernel with one wave per SIMD and 32-query tiles (head dims 128, (192, 128): N % 128 = 0; 64:
 // N % 256 = 0; fixed length, with or without the causal mask); -D and the base-2 LSE must be in the workspace.
 int launch_bwd_dkdv_t32(const BwdArgs& a);
+// The dQ kernel with one wave per SIMD and 32 queries per wave (head dims 128 and (192, 128), fixed length,
+// N % 128 = 0); it also leaves -D and the base-2 LSE of every row in the workspace.
+int launch_bwd_dq_t32(const BwdArgs& a);
 // cu[b] = b * N for b = 0 .. B (device): the equal-length batch as a packed one.
 int launch_uniform_cu(int* cu, int B, int N, void* stream);
 // Fills the two plan tables of the variable-length entry points on the device: 0 or -3.
