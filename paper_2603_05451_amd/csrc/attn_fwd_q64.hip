@@ -17,12 +17,10 @@ namespace attn {
 #undef ATTN_ELEM8
 #undef ATTN_ELEM4
 #define ATTN_MFMA "v_mfma_f32_32x32x16_bf16"
-#define ATTN_Q64_LOG2_BOUND 40
 #define ATTN_Q64_REPAIR 1
 typedef bf16x2 elem2;
 #include "attn_fwd_q64_kernel.inc"
 #undef ATTN_MFMA
-#undef ATTN_Q64_LOG2_BOUND
 #undef ATTN_Q64_REPAIR
 #include "attn_fwd_q64_launch.inc"
 
@@ -35,12 +33,10 @@ namespace f16k {
 #undef ATTN_ELEM8
 #undef ATTN_ELEM4
 #define ATTN_MFMA "v_mfma_f32_32x32x16_f16"
-#define ATTN_Q64_LOG2_BOUND 8
 #define ATTN_Q64_REPAIR 0
 typedef __attribute__((ext_vector_type(2))) _Float16 elem2;
 #include "attn_fwd_q64_kernel.inc"
 #undef ATTN_MFMA
-#undef ATTN_Q64_LOG2_BOUND
 #undef ATTN_Q64_REPAIR
 #include "attn_fwd_q64_launch.inc"
 }  // namespace f16k

@@ -136,8 +136,8 @@ def test_bwd_full_size_one_complete_group(oracle, w):
 def test_bwd_heavy_tailed_full_size(oracle):
     """The (192, 128) workload at N = 32768 with 1 % of the q, k entries multiplied by 8: one head with
     all 32768 query rows through the oracle (about a minute of CPU), dK and dV compared on the first
-    256 keys and on 256 keys drawn at random, dQ on sampled rows; under the term-scaled gate, audited
-    against the bf16-rounded definition (parity.py)."""
+    256 keys and on 256 keys drawn at random, dQ on every row of the head; under the term-scaled gate,
+    audited against the bf16-rounded definition (parity.py)."""
     w = I.MLA_OUTLIER
     x = I.make_inputs(w)
     dq, dk, dv = gpu_fwd_bwd(w, x)
@@ -150,25 +150,26 @@ def test_bwd_heavy_tailed_full_size(oracle):
     rdq, rdk, rdv = oracle.attn_bwd(q, k, v, do, w.scale, True)
     rng = np.random.default_rng(55)
     keys = np.unique(np.concatenate([np.arange(256), rng.integers(256, w.N, 256)]))
-    rows = np.unique(np.concatenate([[0, 1, 63, 64, 255, 256, w.N - 257, w.N - 1], rng.integers(0, w.N, 56)]))
     # magnitudes of the summed terms and the bf16-rounded definition: dQ is separable by query row;
     # dK / dV of a key collect every later query row, accumulated over blocks of rows
-    a_dk = np.zeros((w.N, w.dqk)); a_dv = np.zeros((w.N, w.dv))
-    r_dk = np.zeros((w.N, w.dqk)); r_dv = np.zeros((w.N, w.dv))
+    a_dk = np.zeros((w.N, w.dqk)); a_dv = np.zeros((w.N, w.dv)); a_dq = np.zeros((w.N, 1, w.dqk))
+    r_dk = np.zeros((w.N, w.dqk)); r_dv = np.zeros((w.N, w.dv)); r_dq = np.zeros((w.N, 1, w.dqk))
     from parity import to_bf16
     for lo in range(0, w.N, 2048):
         r = np.arange(lo, lo + 2048)
         args = (q[0, r], k[0, :, 0], v[0, :, 0], do[0, r], w.scale, True)
-        _, _, ak, av = term_magnitudes(*args, q_pos=r)
+        _, a_dq[r], ak, av = term_magnitudes(*args, q_pos=r)
         a_dk += ak; a_dv += av
-        _, _, rk, rv = rounded_reference(*args, q_pos=r, round_kv=False)
+        _, r_dq[r], rk, rv = rounded_reference(*args, q_pos=r, round_kv=False)
         r_dk += rk; r_dv += rv
     r_dk, r_dv = to_bf16(r_dk), to_bf16(r_dv)
     assert_close_terms(dk[b, keys, kvh], rdk[0, keys, 0], a_dk[keys], "dK first 256 + random 256 keys, heavy tails", r_dk[keys])
     assert_close_terms(dv[b, keys, kvh], rdv[0, keys, 0], a_dv[keys], "dV first 256 + random 256 keys, heavy tails", r_dv[keys])
-    args = (q[0, rows], k[0, :, 0], v[0, :, 0], do[0, rows], w.scale, True)
-    a_dq = term_magnitudes(*args, q_pos=rows)[1]
-    r_dq = rounded_reference(*args, q_pos=rows)[1]
-    assert_close_terms(dq[b, rows, h:h + 1], rdq[0, rows], a_dq, "dQ rows, heavy tails", r_dq)
-    # a fixed ceiling on the plain maximum error next to the scaled gate (observed 7.8e-2 for dQ)
-    assert np.abs(dq[b, rows, h:h + 1] - rdq[0, rows]).max() <= 0.10
+    # every row: a relative Frobenius error over a few dozen rows of this workload is set by the two or three
+    # rows whose softmax sits on one key (dS_ij = P_ij (dP_ij - D_i) cancels there and carries the whole
+    # rounding error of D_i), so it is taken over the head
+    assert_close_terms(dq[b, :, h:h + 1], rdq[0], a_dq, "dQ every row of one head, heavy tails", r_dq)
+    # a ceiling on the plain maximum error next to the scaled gate: twice what the roundings the method
+    # prescribes cost the definition itself on the same rows
+    worst, worst_rounded = np.abs(dq[b, :, h:h + 1] - rdq[0]).max(), np.abs(r_dq - rdq[0]).max()
+    assert worst <= 2.0 * worst_rounded, f"dQ max error {worst:.3e}, of the bf16-rounded definition {worst_rounded:.3e}"

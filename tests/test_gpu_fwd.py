@@ -127,3 +127,28 @@ def test_fwd_growing_scores_restart_with_exact_maxima(oracle, causal, N, d, dv):
     assert_close(o[:, rows], ro, f"O growing scores causal={causal}")
     err = np.abs(lse[:, :, rows] - rlse).max()
     assert err <= LSE_ABS, f"LSE growing scores: {err:.3e} (values up to {np.abs(rlse).max():.0f})"
+
+
+@pytest.mark.parametrize("causal,N,d,dv", [(False, 4096, 128, 128), (True, 8192, 192, 128), (False, 8192, 64, 64)])
+def test_fwd_reference_steps_inside_the_pipelined_loop(oracle, causal, N, d, dv):
+    """Scores that climb along the key axis by about 300 binary orders in small steps: relative to the first
+    tile's maximum the tile sums pass 2^90 several times without ever becoming infinite, so the kernel
+    with 64 queries per wave must raise its reference inside the pipelined loop (the rescale of paper
+    Sec. 3.1.4 with a power-of-two step); no second pass is involved.  Every 37th row against the oracle."""
+    import paper_2603_05451_amd as A
+    g = torch.Generator("cpu").manual_seed(78)
+    H = 2
+    climb = torch.linspace(0.0, 300.0 / (1.4427 * d ** 0.5), N).view(1, N, 1, 1)         # score = sqrt(d) * climb
+    q = (1.0 + 0.1 * torch.randn(1, N, H, d, generator=g)).to(torch.bfloat16)
+    k = (climb + 0.1 * torch.randn(1, N, 1, d, generator=g)).to(torch.bfloat16)
+    v = torch.randn(1, N, 1, dv, generator=g).to(torch.bfloat16)
+    scale = d ** -0.5
+    o, lse = A.attn_fwd(q.cuda(), k.cuda(), v.cuda(), scale, causal)
+    torch.cuda.synchronize()
+    o, lse = o.float().cpu().numpy(), lse.cpu().numpy()
+    assert np.isfinite(o).all() and np.isfinite(lse).all()
+    rows = np.unique(np.concatenate([[0, 1, 255, 256, N - 257, N - 1], np.arange(5, N, 37)]))
+    ro, rlse = oracle.attn_fwd(I.to_f64(q[:, rows]), I.to_f64(k), I.to_f64(v), scale, causal, q_pos=rows)
+    assert_close(o[:, rows], ro, f"O climbing scores causal={causal} d={d}")
+    err = np.abs(lse[:, :, rows] - rlse).max()
+    assert err <= LSE_ABS * max(1.0, np.abs(rlse).max() / 64), f"LSE climbing scores: {err:.3e} (values up to {np.abs(rlse).max():.0f})"
