@@ -22,7 +22,7 @@ PEAK_BF16_TFLOPS = 2500.0      # MI355X published dense bf16 MFMA peak
 # --pmc runs, scaled by the same counters' reading for a 1 GiB copy; profiles/bench_target_*.md).
 # They cannot be measured from inside this process; None for any other workload.
 MEASURED_TRAFFIC = {
-    "target_N8192_d128_nc": {"attn_fwd_q64_kernel": 208e6 + 74e6, "attn_bwd_dkdv_t32_kernel": 407e6 + 134e6,
+    "target_N8192_d128_nc": {"attn_fwd_q64_kernel": 202e6 + 68e6, "attn_bwd_dkdv_t32_kernel": 407e6 + 134e6,
                              "attn_bwd_dq_q64_kernel": 337e6 + 69e6},
 }
 PAPER_CONTEXT = "paper: up to 1613 TFLOP/s forward (71% of 2.25 PFLOP/s) on B200, BF16 -- other hardware, context only"
