@@ -88,11 +88,12 @@ int launch_bwd(const BwdArgs& a)
     };
     const bool d128 = a.d_qk == 128 && a.d_v == 128, d64 = a.d_qk == 64 && a.d_v == 64, d192 = a.d_qk == 192 && a.d_v == 128;
     // below these lengths the 4-wave dQ kernel wins (its blocks are half the size and fill the chip better);
-    // at d = 64 the 256-key blocks of the dK/dV kernel are too few on short sequences
+    // at d = 64 the 256-key blocks of the dK/dV kernel are too few on short sequences (measured against the
+    // 4-wave kernel: +10 % at N = 512, +1 % at N = 1024, -4 % at N = 2048; under the mask +4 % at N = 4096, -6 % at N = 8192)
     const bool dq_q64 = (a.phases & 4) && !a.plan && a.N % 256 == 0 &&
                         ((d128 && a.N >= (a.causal ? 4096 : 1024)) || (d64 && a.N >= (a.causal ? 8192 : 2048)));
     const bool dkdv_t32 = (a.phases & 2) && !a.plan &&
-                          (((d128 || d192) && a.N % 128 == 0) || (d64 && a.N % 256 == 0 && a.N >= (a.causal ? 4096 : 512)));
+                          (((d128 || d192) && a.N % 128 == 0) || (d64 && a.N % 256 == 0 && a.N >= (a.causal ? 8192 : 2048)));
     // (192, 128): the 64-query kernel's fragments and accumulators do not fit; 32 queries per wave, pipelined
     const bool dq_t32 = (a.phases & 4) && !a.plan && d192 && a.N % 128 == 0 && a.N >= (a.causal ? 1024 : 512);
     if (!dq_q64 && !dq_t32 && !dkdv_t32) return generic(a.phases);

@@ -38,6 +38,8 @@ SMALL = [
     # per wave for dK / dV), GQA with three heads per group, 8 and 9 blocks of 256 rows
     I.Workload("s_d64_nc_2048_gqa", 1, 3, 1, 2048, 64, 64, False, 18),
     I.Workload("s_d64_nc_2304", 2, 2, 2, 2304, 64, 64, False, 17),
+    # d = 64 under the causal mask: the one-wave-per-SIMD kernels start at N = 8192 (two query heads per KV head)
+    I.Workload("s_d64_c_8192_gqa", 1, 2, 1, 8192, 64, 64, True, 14),
     # (192, 128) from N = 1024 with the causal mask and N = 512 without: the one-wave dQ kernel with 32 queries per wave
     I.Workload("s_d192_c_1024_gqa", 1, 3, 1, 1024, 192, 128, True, 16),
     I.Workload("s_d192_nc_640", 2, 2, 2, 640, 192, 128, False, 15),
