@@ -230,7 +230,7 @@ def main():
     f_dq = 2.0 * pairs * (2 * w.dqk + w.dv)           # S, dQ over d_qk; dP over d_v
     tf = lambda flops, ms: flops / ms / 1e9
     t32 = ((w.dqk, w.dv) in ((128, 128), (192, 128)) and w.N % 128 == 0) or \
-          ((w.dqk, w.dv) == (64, 64) and w.N % 256 == 0 and w.N >= (4096 if w.causal else 512))
+          ((w.dqk, w.dv) == (64, 64) and w.N % 256 == 0 and w.N >= (8192 if w.causal else 2048))
     dkdv_name = ("attn_bwd_dkdv_t32_kernel" if t32 else
                  "attn_bwd_dkdv_ws_kernel" if w.dqk in (96, 128) else "attn_bwd_dkdv_kernel")
     # on long sequences with N % 256 == 0 the library runs 256-query blocks with 64 queries per wave:

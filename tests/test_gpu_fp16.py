@@ -23,6 +23,7 @@ CASES = [
     I.Workload("h_d128_nc_2048_gqa", 1, 2, 1, 2048, 128, 128, False, 68),
     I.Workload("h_d128_c_4096", 1, 1, 1, 4096, 128, 128, True, 69),
     I.Workload("h_d64_nc_2048", 1, 2, 1, 2048, 64, 64, False, 71),
+    I.Workload("h_d192_nc_2048_gqa", 1, 2, 1, 2048, 192, 128, False, 72),
 ]
 
 
