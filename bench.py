@@ -216,6 +216,17 @@ def main():
     ms_prep = event_ms(lambda: bwd(A.ATTN_BWD_PREPARE), n)
     ms_dkdv = event_ms(lambda: bwd(A.ATTN_BWD_DKDV), n)
     ms_dq = event_ms(lambda: bwd(A.ATTN_BWD_DQ), n)
+    # the same kernels timed where they run in a step: n more steps with an event after every kernel
+    # (attn_bwd split into its two phases, which compose bit for bit: the same two launches in the same order)
+    marks = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(n)]
+    for m in marks:
+        m[0].record(); fwd()
+        m[1].record(); bwd(A.ATTN_BWD_DQ)
+        m[2].record(); bwd(A.ATTN_BWD_DKDV)
+        m[3].record()
+    torch.cuda.synchronize()
+    in_step = [sum(m[i].elapsed_time(m[i + 1]) for m in marks) / n for i in range(3)]
+    ms_fwd_step, ms_dq_step, ms_dkdv_step = in_step
     bwd()                                    # leave consistent outputs behind
     torch.cuda.synchronize()
     if args.copy_calibration:
@@ -261,16 +272,19 @@ def main():
                 "frac_of_peak": round(tf(f_bwd, ms_bwd) / PEAK_BF16_TFLOPS, 4),
                 "ms_prepare": round(ms_prep, 4), "ms_dkdv": round(ms_dkdv, 4), "ms_dq": round(ms_dq, 4),
                 "ms_prepare_kernel_alone": round(ms_prep_alone, 4)},
+        # each kernel's average duration inside a step (events between the kernels of n steps); the figures
+        # in "fwd" / "bwd" above time each call in a loop of its own, back to back
+        "in_step": {"ms_fwd": round(ms_fwd_step, 4), "ms_dq": round(ms_dq_step, 4), "ms_dkdv": round(ms_dkdv_step, 4)},
         # dominant kernel = the dK/dV kernel.  Its ALGORITHMIC
         # work is what it executes on the MFMA units: four contractions (S, dP, dV, dK) of
-        # N^2 (d_qk or d_v) multiply-adds each.
+        # N^2 (d_qk or d_v) multiply-adds each.  Duration: the kernel's average inside the steps.
         "roofline": {"kernel": dkdv_name, "bound": "mfma",
-                     "achieved": round(tf(f_dkdv, ms_dkdv), 1), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                     "frac": round(tf(f_dkdv, ms_dkdv) / PEAK_BF16_TFLOPS, 4),
+                     "achieved": round(tf(f_dkdv, ms_dkdv_step), 1), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                     "frac": round(tf(f_dkdv, ms_dkdv_step) / PEAK_BF16_TFLOPS, 4),
                      "traffic": MEASURED_TRAFFIC.get(w.name, {}).get(dkdv_name)},
         "roofline_dq": {"kernel": dq_name, "bound": "mfma",
-                        "achieved": round(tf(f_dq, ms_dq), 1), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                        "frac": round(tf(f_dq, ms_dq) / PEAK_BF16_TFLOPS, 4),
+                        "achieved": round(tf(f_dq, ms_dq_step), 1), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                        "frac": round(tf(f_dq, ms_dq_step) / PEAK_BF16_TFLOPS, 4),
                         "traffic": MEASURED_TRAFFIC.get(w.name, {}).get(dq_name)},
         "roofline_fwd": {"kernel": fwd_name, "bound": "mfma", "achieved": round(tf(f_fwd, ms_fwd), 1),
                          "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
